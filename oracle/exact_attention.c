@@ -1,0 +1,156 @@
+/*
+ * TEST INFRASTRUCTURE -- not part of the product path.
+ *
+ * Plain fp64 CPU definition of decode-phase softmax attention (the paper's
+ * Eq. 1 in Section 2.1, with N_q = 1 as in the decode column of Table 1):
+ *
+ *     s_t  = scale * sum_j q[j] * k[t][j]          for t < N
+ *     w_t  = exp(s_t - max_t s_t)
+ *     out  = (sum_t w_t * v[t]) / (sum_t w_t)
+ *     lse  = max_t s_t + log(sum_t w_t)             (the L of Algorithm 2)
+ *
+ * Two passes over the context, no tiling, no splitting, no re-scaling
+ * operator: this is the result LeanAttention must reach exactly (Section 4.1
+ * claims the split/merge gives the same exact output for any split).
+ *
+ * Inputs are the raw 16-bit patterns (IEEE binary16 or bfloat16) the GPU
+ * path reads, widened exactly to double, or plain doubles for hand-made
+ * pins.  A query head h_q reads KV head h_q / (Hq / Hkv).
+ *
+ * Only tests, the smoke check and the benchmark's cpu_baseline leg call this
+ * file.  It shares no code with the HIP path.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F16 = 0, ORACLE_BF16 = 1, ORACLE_F64 = 2 };
+enum { ORACLE_KV_PADDED = 0, ORACLE_KV_PACKED = 1 };
+
+static double widen_bf16(uint16_t bits) {
+    uint32_t u = ((uint32_t)bits) << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+static double widen_f16(uint16_t bits) {
+    int sign = (bits >> 15) & 1;
+    int expo = (bits >> 10) & 0x1f;
+    int frac = bits & 0x3ff;
+    double mag;
+    if (expo == 0) {
+        mag = ldexp((double)frac, -24); /* zero and subnormals */
+    } else if (expo == 31) {
+        mag = frac ? NAN : INFINITY;
+    } else {
+        mag = ldexp((double)(1024 + frac), expo - 25);
+    }
+    return sign ? -mag : mag;
+}
+
+/* Widen one row of D elements starting at element offset `row_off`. */
+static void widen_row(const void* base, int64_t row_off, int D, int dtype, double* dst) {
+    if (dtype == ORACLE_F64) {
+        memcpy(dst, (const double*)base + row_off, (size_t)D * sizeof(double));
+        return;
+    }
+    const uint16_t* p = (const uint16_t*)base + row_off;
+    for (int j = 0; j < D; ++j) dst[j] = dtype == ORACLE_BF16 ? widen_bf16(p[j]) : widen_f16(p[j]);
+}
+
+/*
+ * One (query row, context) pair: `k_rows`/`v_rows` point at element offset
+ * `kv_off` of the first cached row; rows are D elements apart.
+ * `scores` is caller scratch of n doubles, `row` of D doubles.
+ */
+static void attend_one(const void* q, int64_t q_off, const void* k_rows, const void* v_rows,
+                       int64_t kv_off, int64_t n, int D, int dtype, double scale, double* scores,
+                       double* row, double* qrow, double* out, double* lse) {
+    for (int j = 0; j < D; ++j) out[j] = 0.0;
+    if (n <= 0) { /* empty context: defined as zeros, lse = -inf */
+        if (lse) *lse = -INFINITY;
+        return;
+    }
+    widen_row(q, q_off, D, dtype, qrow);
+    double smax = -INFINITY;
+    for (int64_t t = 0; t < n; ++t) {
+        widen_row(k_rows, kv_off + t * D, D, dtype, row);
+        double dot = 0.0;
+        for (int j = 0; j < D; ++j) dot += qrow[j] * row[j];
+        scores[t] = scale * dot;
+        if (scores[t] > smax) smax = scores[t];
+    }
+    double z = 0.0;
+    for (int64_t t = 0; t < n; ++t) {
+        double w = exp(scores[t] - smax);
+        z += w;
+        widen_row(v_rows, kv_off + t * D, D, dtype, row);
+        for (int j = 0; j < D; ++j) out[j] += w * row[j];
+    }
+    for (int j = 0; j < D; ++j) out[j] /= z;
+    if (lse) *lse = smax + log(z);
+}
+
+/*
+ * q   : [B, Hq, D]
+ * k,v : PADDED [B, Hkv, n_stride, D]  (row t of (b,h) at ((b*Hkv+h)*n_stride + t)*D), or
+ *       PACKED [Hkv, total, D] with total = sum(seqlens), sequence b starting at
+ *       row cu[b] = sum_{b'<b} seqlens[b'] (n_stride ignored)
+ * out : [B, Hq, D] doubles;  lse: [B, Hq] doubles or NULL
+ * Returns the number of threads used, or a negative value for bad arguments.
+ */
+int oracle_decode_attention(const void* q, const void* k, const void* v, const int32_t* seqlens,
+                            int B, int Hq, int Hkv, int D, int dtype, int kv_layout,
+                            int64_t n_stride, double scale, double* out, double* lse,
+                            int n_threads) {
+    if (!q || !k || !v || !seqlens || !out) return -1;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv != 0) return -2;
+    if (dtype < 0 || dtype > 2 || kv_layout < 0 || kv_layout > 1) return -3;
+    int64_t total = 0, nmax = 0;
+    int64_t* cu = (int64_t*)malloc((size_t)(B + 1) * sizeof(int64_t));
+    if (!cu) return -4;
+    for (int b = 0; b < B; ++b) {
+        if (seqlens[b] < 0) { free(cu); return -5; }
+        cu[b] = total;
+        total += seqlens[b];
+        if (seqlens[b] > nmax) nmax = seqlens[b];
+    }
+    cu[B] = total;
+    if (kv_layout == ORACLE_KV_PADDED && n_stride < nmax) { free(cu); return -6; }
+    const int group = Hq / Hkv;
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads > 0) omp_set_num_threads(n_threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+#endif
+        double* scores = (double*)malloc((size_t)(nmax > 0 ? nmax : 1) * sizeof(double));
+        double* row = (double*)malloc((size_t)D * sizeof(double));
+        double* qrow = (double*)malloc((size_t)D * sizeof(double));
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 1)
+#endif
+        for (int64_t bh = 0; bh < (int64_t)B * Hq; ++bh) {
+            int b = (int)(bh / Hq), hq = (int)(bh % Hq), h = hq / group;
+            int64_t kv_off = kv_layout == ORACLE_KV_PADDED
+                                 ? ((int64_t)(b * (int64_t)Hkv + h) * n_stride) * D
+                                 : ((int64_t)h * total + cu[b]) * D;
+            attend_one(q, bh * D, k, v, kv_off, seqlens[b], D, dtype, scale, scores, row, qrow,
+                       out + bh * D, lse ? lse + bh : NULL);
+        }
+        free(scores);
+        free(row);
+        free(qrow);
+#ifdef _OPENMP
+    }
+#endif
+    free(cu);
+    return used;
+}
