@@ -1,0 +1,176 @@
+/*
+ * lean_attn.h -- C ABI of the MI355X (gfx950) LeanAttention decode library.
+ *
+ * Decode-phase attention (Section 2.1, Eq. 1 with N_q = 1; Table 1, decode
+ * column): for every sequence b and query head h_q one query row attends over
+ * the N_b cached K/V rows of KV head h_q / (Hq / Hkv):
+ *
+ *     out[b,h_q,:] = softmax(scale * q[b,h_q,:] . K[b,h,:N_b,:]^T) V[b,h,:N_b,:]
+ *
+ * The work is decomposed stream-K style (Section 4.3): the LeanTile iterations
+ * of all (sequence, KV head) output tiles are laid on one line and cut into
+ * equal contiguous spans, one per workgroup of a persistent grid; partial
+ * (O~, m, l) triples are merged with the softmax re-scaling operator of
+ * Section 4.1 inside the same launch (Algorithm 2).
+ *
+ * All pointers named "device" are HIP device pointers on the current device;
+ * "host" pointers are ordinary host memory.  No function takes ownership of
+ * any buffer and no function allocates device memory.  Calls are asynchronous
+ * on the given stream unless stated otherwise.  Every function returns
+ * LEAN_ATTN_OK (0) or a negative lean_attn_status; on error nothing is
+ * launched.  No exception or abort crosses this boundary.
+ */
+#ifndef LEAN_ATTN_H_
+#define LEAN_ATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum lean_attn_status {
+    LEAN_ATTN_OK = 0,
+    LEAN_ATTN_ERR_NULL_POINTER = -1,  /* a required pointer is NULL */
+    LEAN_ATTN_ERR_BAD_SHAPE = -2,     /* B, Hq, Hkv <= 0, Hq % Hkv != 0, group > 16 */
+    LEAN_ATTN_ERR_UNSUPPORTED = -3,   /* head dim / dtype / layout not built */
+    LEAN_ATTN_ERR_WORKSPACE = -4,     /* workspace missing, misaligned or too small */
+    LEAN_ATTN_ERR_SEQLEN = -5,        /* a negative length, N_b*D*2 >= 2^31 bytes, or a padded stride below the longest */
+    LEAN_ATTN_ERR_BATCH_TOO_LARGE = -6, /* B > LEAN_ATTN_MAX_BATCH */
+    LEAN_ATTN_ERR_HIP = -7,           /* a HIP runtime call failed (no device, bad stream, ...) */
+    LEAN_ATTN_ERR_TUNING = -8,        /* a lean_attn_tuning field is out of range */
+    LEAN_ATTN_ERR_PEER_TIMEOUT = -9   /* reported by lean_attn_workspace_status only */
+} lean_attn_status;
+
+/* Element type of q, k_cache and v_cache (the output is always fp32). */
+typedef enum lean_attn_dtype { LEAN_ATTN_F16 = 0, LEAN_ATTN_BF16 = 1 } lean_attn_dtype;
+
+/*
+ * KV-cache layouts.
+ * PADDED: [B, Hkv, kv_seq_stride, D]; row t of (b, h) starts at element
+ *         ((b*Hkv + h)*kv_seq_stride + t)*D.  This is the constant-head-stride
+ *         view Section 4.3 requires.  Rows t >= N_b are never read.
+ * PACKED: [Hkv, sum_b N_b, D], no batch dimension; sequence b starts at row
+ *         cu[b] = sum_{b'<b} N_b' (the ragged form of Section 4.3, "Lean Ragged
+ *         Batching").  kv_seq_stride is ignored.
+ */
+typedef enum lean_attn_kv_layout { LEAN_ATTN_KV_PADDED = 0, LEAN_ATTN_KV_PACKED = 1 } lean_attn_kv_layout;
+
+#define LEAN_ATTN_MAX_BATCH 256  /* sequences per call (the schedule table travels as kernel arguments) */
+#define LEAN_ATTN_MAX_GROUP 16   /* query heads per KV head (rows of one MFMA tile) */
+#define LEAN_ATTN_MAX_GRID 2048  /* upper bound on workgroups; sizes the workspace */
+
+/*
+ * The stream-K schedule of one call (Section 4.3 and the first lines of
+ * Algorithm 2).  Output tile = one (sequence, KV head) pair; it owns
+ * ceil(N_b / T_n) LeanTile iterations.  CTA g owns iterations
+ * [g*iters_per_cta + min(g, extra), ... + iters_per_cta + (g < extra)).
+ */
+typedef struct lean_attn_plan {
+    int32_t T_n;              /* LeanTile size in tokens */
+    int32_t T_m;              /* query rows per output tile = Hq / Hkv */
+    int32_t num_output_tiles; /* B * Hkv, including tiles of empty sequences */
+    int32_t grid;             /* G: workgroups launched, <= max_resident and <= total_iters */
+    int64_t total_iters;      /* I: LeanTile iterations over all output tiles */
+    int64_t iters_per_cta;    /* floor(I / G) */
+    int32_t extra;            /* I mod G: the first `extra` CTAs take one more iteration */
+    int32_t block_threads;    /* workgroup size */
+    int32_t max_resident;     /* compute units x workgroups resident per unit */
+    int32_t kernel;           /* 0 = VALU single-row kernel (Hq == Hkv), 1 = MFMA query-group kernel */
+} lean_attn_plan;
+
+/*
+ * Optional overrides, for tests and sweeps.  A zero field means "library
+ * default".  Results never depend on these (Section 4.1: any split gives the
+ * same attention output); only the balance does.
+ */
+typedef struct lean_attn_tuning {
+    int32_t grid;          /* force G (clipped to I); must not exceed what is co-resident */
+    int32_t ctas_per_cu;   /* workgroups per compute unit used to size the default G */
+    int32_t num_cus;       /* pretend the device has this many compute units (schedule queries) */
+    int32_t kernel;        /* 0 default, 1 force VALU kernel (needs Hq == Hkv), 2 force MFMA kernel */
+    int32_t xcd_remap;     /* 0 default, 1 off, 2 on: place consecutive spans on one XCD */
+    int32_t spin_limit;    /* polls before a waiting host CTA gives up and reports PEER_TIMEOUT */
+} lean_attn_tuning;
+
+/*
+ * Bytes of device workspace lean_attn_decode needs for this problem shape:
+ * arrival flags plus one partial (O~[T_m, D], m[T_m], l[T_m]) slot per CTA, as
+ * in Algorithm 2 ("Op[g], mp[g], lp[g], flags[g]").  Host-only arithmetic; it
+ * does not depend on the device.  Returns 0 for an unsupported shape.
+ */
+size_t lean_attn_workspace_size(int B, int Hq, int Hkv, int D, int dtype);
+
+/*
+ * Clear the flags of a freshly allocated workspace (device pointer, 256-byte
+ * aligned).  Needed once per allocation: every decode call leaves the flags
+ * cleared again.  A workspace must not be shared by two calls in flight.
+ */
+int lean_attn_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Blocking: waits for `hip_stream`, then reports LEAN_ATTN_ERR_PEER_TIMEOUT if
+ * a host CTA of an earlier call on this workspace gave up waiting for a peer
+ * (its output rows are then invalid), else LEAN_ATTN_OK.  Clears the report and,
+ * after a timeout, all flags, so the workspace can be used again.
+ */
+int lean_attn_workspace_status(void* workspace, void* hip_stream);
+
+/*
+ * Host-only: the schedule lean_attn_decode would use.  `seqlens` is a host
+ * array of B context lengths (N_b counts the current token, whose K/V row is
+ * already in the cache).  With tuning->num_cus > 0 no device is queried, so
+ * this runs without a GPU.  `tuning` may be NULL.
+ */
+int lean_attn_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, int dtype,
+                       int kv_layout, const lean_attn_tuning* tuning, lean_attn_plan* plan);
+
+/*
+ * Host-only: the output-tile segments CTA `g` walks under `plan` (the loop of
+ * Algorithm 2), computed by the same code the kernel runs.  Writes up to
+ * `max_segments` records of 8 int64 each:
+ *   {tile_idx, b, h_kv, local_iter, local_iter_end, host_block, finishing_block, last_cta}
+ * (last_cta is -1 unless host and not finishing) and returns the number of
+ * segments, or a negative status.
+ */
+int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, int Hkv,
+                   int kv_layout, int g, int64_t* segments, int max_segments);
+
+/*
+ * Decode attention.
+ *   q        device, [B, Hq, D], 16-bit elements of `dtype`, contiguous
+ *   k_cache  device, layout per `kv_layout`, same element type
+ *   v_cache  device, same layout as k_cache
+ *   seqlens  HOST, B int32 context lengths N_b >= 0 (N_b = 0: that row's out is 0, lse -inf)
+ *   out      device, [B, Hq, D] fp32
+ *   lse      device, [B, Hq] fp32, or NULL: L = m + log(l) of Algorithm 2
+ *   workspace, workspace_bytes  device scratch from lean_attn_workspace_size, initialised once
+ *   kv_seq_stride  rows between consecutive (b, h) slabs in the PADDED layout
+ *   scale    multiplies q.k before the softmax (1/sqrt(D) in Eq. 1)
+ *   tuning   NULL for defaults
+ * Supported: D in {64, 128}, both dtypes, Hq/Hkv <= 16, B <= LEAN_ATTN_MAX_BATCH.
+ * q, k_cache, v_cache must be 16-byte aligned.
+ */
+int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache,
+                     const int32_t* seqlens, float* out, float* lse, void* workspace,
+                     size_t workspace_bytes, int B, int Hq, int Hkv, int D, int kv_layout,
+                     int64_t kv_seq_stride, float scale, int dtype, const lean_attn_tuning* tuning,
+                     void* hip_stream);
+
+/*
+ * Measurement helper: one pass of 16-byte loads over `bytes` of device memory
+ * by a persistent grid of `grid` workgroups, each reading one contiguous share
+ * (the access pattern of the decode kernel without its arithmetic).  Used to
+ * report the streaming-read ceiling of the machine next to the decode rate.
+ * `sink` is a device pointer to at least 4 bytes.  bytes must be a multiple of 16.
+ */
+int lean_attn_read_probe(const void* buf, size_t bytes, void* sink, int grid, void* hip_stream);
+
+/* Static description of a status code. */
+const char* lean_attn_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LEAN_ATTN_H_ */

@@ -1,0 +1,189 @@
+"""Thin ctypes binding over the C ABI of ``include/lean_attn.h``.
+
+Argument marshalling only: every step of the decode path runs in the HIP
+library.  There is no fallback: if the library cannot be loaded the import of
+a function raises.  Tensors are torch tensors used purely as device memory;
+the stream is torch's current HIP stream unless one is given.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+from . import build as _build
+
+F16, BF16 = 0, 1
+KV_PADDED, KV_PACKED = 0, 1
+MAX_BATCH, MAX_GROUP, MAX_GRID = 256, 16, 2048
+
+OK = 0
+ERR_NULL_POINTER, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE = -1, -2, -3, -4
+ERR_SEQLEN, ERR_BATCH_TOO_LARGE, ERR_HIP, ERR_TUNING, ERR_PEER_TIMEOUT = -5, -6, -7, -8, -9
+
+
+class Plan(ctypes.Structure):
+    _fields_ = [
+        ("T_n", ctypes.c_int32), ("T_m", ctypes.c_int32), ("num_output_tiles", ctypes.c_int32),
+        ("grid", ctypes.c_int32), ("total_iters", ctypes.c_int64), ("iters_per_cta", ctypes.c_int64),
+        ("extra", ctypes.c_int32), ("block_threads", ctypes.c_int32), ("max_resident", ctypes.c_int32),
+        ("kernel", ctypes.c_int32),
+    ]
+
+
+class Tuning(ctypes.Structure):
+    _fields_ = [
+        ("grid", ctypes.c_int32), ("ctas_per_cu", ctypes.c_int32), ("num_cus", ctypes.c_int32),
+        ("kernel", ctypes.c_int32), ("xcd_remap", ctypes.c_int32), ("spin_limit", ctypes.c_int32),
+    ]
+
+
+class LeanAttnError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"lean_attn status {status}: {lean_attn_strerror(status)}")
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIBRARY
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.LIBRARY
+    if not os.path.exists(path):
+        _build.build()
+    lib = ctypes.CDLL(path)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+    lib.lean_attn_workspace_size.restype = sz
+    lib.lean_attn_workspace_size.argtypes = [i32] * 5
+    lib.lean_attn_workspace_init.restype = i32
+    lib.lean_attn_workspace_init.argtypes = [vp, sz, vp]
+    lib.lean_attn_workspace_status.restype = i32
+    lib.lean_attn_workspace_status.argtypes = [vp, vp]
+    lib.lean_attn_schedule.restype = i32
+    lib.lean_attn_schedule.argtypes = [vp, i32, i32, i32, i32, i32, i32, ctypes.POINTER(Tuning), ctypes.POINTER(Plan)]
+    lib.lean_attn_walk.restype = i32
+    lib.lean_attn_walk.argtypes = [ctypes.POINTER(Plan), vp, i32, i32, i32, i32, vp, i32]
+    lib.lean_attn_decode.restype = i32
+    lib.lean_attn_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i32, i32, i32, i32, i32, i64,
+                                     ctypes.c_float, i32, ctypes.POINTER(Tuning), vp]
+    lib.lean_attn_read_probe.restype = i32
+    lib.lean_attn_read_probe.argtypes = [vp, sz, vp, i32, vp]
+    lib.lean_attn_strerror.restype = ctypes.c_char_p
+    lib.lean_attn_strerror.argtypes = [i32]
+    _lib = lib
+    return lib
+
+
+def _seqlens_array(seqlens: Sequence[int]):
+    arr = (ctypes.c_int32 * len(seqlens))(*[int(x) for x in seqlens])
+    return arr
+
+
+def _tuning_ptr(tuning: Optional[Tuning]):
+    return ctypes.byref(tuning) if tuning is not None else None
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        import torch
+
+        return torch.cuda.current_stream().cuda_stream
+    return int(getattr(stream, "cuda_stream", stream))
+
+
+def _dtype_code(t) -> int:
+    name = str(t.dtype)
+    if name == "torch.float16":
+        return F16
+    if name == "torch.bfloat16":
+        return BF16
+    raise TypeError(f"q/k/v must be float16 or bfloat16, got {name}")
+
+
+def lean_attn_strerror(status: int) -> str:
+    return _load().lean_attn_strerror(int(status)).decode()
+
+
+def lean_attn_workspace_size(B: int, Hq: int, Hkv: int, D: int, dtype: int) -> int:
+    return int(_load().lean_attn_workspace_size(B, Hq, Hkv, D, dtype))
+
+
+def lean_attn_workspace_init(workspace, stream=None) -> None:
+    rc = _load().lean_attn_workspace_init(workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                          _stream_handle(stream))
+    if rc != OK:
+        raise LeanAttnError(rc)
+
+
+def lean_attn_workspace_status(workspace, stream=None) -> int:
+    return int(_load().lean_attn_workspace_status(workspace.data_ptr(), _stream_handle(stream)))
+
+
+def lean_attn_schedule(seqlens, Hq, Hkv, D, dtype, kv_layout, tuning: Optional[Tuning] = None) -> Plan:
+    plan = Plan()
+    arr = _seqlens_array(seqlens)
+    rc = _load().lean_attn_schedule(arr, len(seqlens), Hq, Hkv, D, dtype, kv_layout, _tuning_ptr(tuning),
+                                    ctypes.byref(plan))
+    if rc != OK:
+        raise LeanAttnError(rc)
+    return plan
+
+
+def lean_attn_walk(plan: Plan, seqlens, Hkv, kv_layout, g, max_segments: int = 4096):
+    """Segments of CTA ``g``: list of dicts (tile_idx, b, h, local_iter, local_iter_end, host, finishing, last_cta)."""
+    arr = _seqlens_array(seqlens)
+    buf = (ctypes.c_int64 * (8 * max_segments))()
+    n = _load().lean_attn_walk(ctypes.byref(plan), arr, len(seqlens), Hkv, kv_layout, g, buf, max_segments)
+    if n < 0:
+        raise LeanAttnError(n)
+    if n > max_segments:
+        raise ValueError(f"CTA {g} walks {n} segments; raise max_segments")
+    keys = ("tile_idx", "b", "h", "local_iter", "local_iter_end", "host", "finishing", "last_cta")
+    return [dict(zip(keys, (int(buf[8 * i + j]) for j in range(8)))) for i in range(n)]
+
+
+def lean_attn_decode(q, k_cache, v_cache, seqlens, out, workspace, *, Hkv: int, kv_layout: int = KV_PADDED,
+                     kv_seq_stride: int = 0, scale: float, lse=None, tuning: Optional[Tuning] = None,
+                     stream=None) -> None:
+    """Launch decode attention on the current (or given) HIP stream.  Shapes as in ``lean_attn.h``."""
+    B, Hq, D = q.shape
+    if not (q.is_cuda and k_cache.is_cuda and v_cache.is_cuda and out.is_cuda and workspace.is_cuda):
+        raise ValueError("q, k_cache, v_cache, out and workspace must be device tensors")
+    if not (q.is_contiguous() and k_cache.is_contiguous() and v_cache.is_contiguous() and out.is_contiguous()):
+        raise ValueError("tensors must be contiguous")
+    if str(out.dtype) != "torch.float32" or tuple(out.shape) != (B, Hq, D):
+        raise ValueError("out must be float32 [B, Hq, D]")
+    if k_cache.dtype != q.dtype or v_cache.dtype != q.dtype or k_cache.shape != v_cache.shape:
+        raise ValueError("k_cache and v_cache must match q's dtype and each other's shape")
+    if len(seqlens) != B:
+        raise ValueError("seqlens must have B entries")
+    total = int(sum(int(x) for x in seqlens))
+    if kv_layout == KV_PADDED:
+        if k_cache.numel() != B * Hkv * kv_seq_stride * D:
+            raise ValueError("PADDED k_cache must be [B, Hkv, kv_seq_stride, D]")
+    elif k_cache.numel() != Hkv * total * D:
+        raise ValueError("PACKED k_cache must be [Hkv, sum(seqlens), D]")
+    if lse is not None and (str(lse.dtype) != "torch.float32" or lse.numel() != B * Hq or not lse.is_cuda):
+        raise ValueError("lse must be a float32 device tensor [B, Hq]")
+    arr = _seqlens_array(seqlens)
+    rc = _load().lean_attn_decode(
+        q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), arr, out.data_ptr(),
+        lse.data_ptr() if lse is not None else None, workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), B, Hq, Hkv, D, kv_layout, int(kv_seq_stride),
+        float(scale), _dtype_code(q), _tuning_ptr(tuning), _stream_handle(stream))
+    if rc != OK:
+        raise LeanAttnError(rc)
+
+
+def lean_attn_read_probe(buf, sink, grid: int, stream=None) -> None:
+    rc = _load().lean_attn_read_probe(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), grid,
+                                      _stream_handle(stream))
+    if rc != OK:
+        raise LeanAttnError(rc)

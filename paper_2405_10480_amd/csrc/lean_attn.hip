@@ -1,0 +1,373 @@
+// Host side of the LeanAttention decode library: argument checks, the
+// stream-K scheduler (Section 4.3), kernel selection and launch.  The C ABI is
+// declared in include/lean_attn.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <mutex>
+
+#include "../../include/lean_attn.h"
+#include "lean_device.h"
+#include "lean_gqa_core.h"
+#include "lean_kernel.h"
+#include "lean_mha_core.h"
+#include "lean_sched.h"
+
+namespace lean {
+
+static_assert(kMaxBatch == LEAN_ATTN_MAX_BATCH, "header and scheduler disagree on the batch limit");
+static_assert(kMaxGrid == LEAN_ATTN_MAX_GRID, "header and workspace layout disagree on the grid limit");
+
+// Kernel variants: core x dtype x head dim.  U = 8 loads of 16 bytes per lane
+// for K and again for V per step (VALU core); 2 blocks of 16 tokens per wave per
+// step (MFMA core).  Four waves per workgroup; LeanTile = 128 tokens at D = 128
+// and 256 (VALU) / 128 (MFMA) at D = 64.
+constexpr int kNW = 4;
+constexpr int kU = 8;
+constexpr int kNBLK = 2;
+constexpr int kDefaultCtasPerCu = 2;
+
+using MhaF16D64 = MhaCore<kDtF16, 64, kU, kNW>;
+using MhaBF16D64 = MhaCore<kDtBF16, 64, kU, kNW>;
+using MhaF16D128 = MhaCore<kDtF16, 128, kU, kNW>;
+using MhaBF16D128 = MhaCore<kDtBF16, 128, kU, kNW>;
+using GqaF16D64 = GqaCore<kDtF16, 64, kNBLK, kNW>;
+using GqaBF16D64 = GqaCore<kDtBF16, 64, kNBLK, kNW>;
+using GqaF16D128 = GqaCore<kDtF16, 128, kNBLK, kNW>;
+using GqaBF16D128 = GqaCore<kDtBF16, 128, kNBLK, kNW>;
+
+struct Variant {
+    const void* fn;
+    int T_n;
+    int threads;
+};
+
+template <class Core>
+static Variant variant_of() {
+    return Variant{reinterpret_cast<const void*>(&lean_decode_kernel<Core>), Core::kTn, Core::kThreads};
+}
+
+// kernel: 0 VALU single-row core, 1 MFMA query-group core
+static bool pick_variant(int kernel, int dtype, int D, Variant* v) {
+    const bool bf = dtype == LEAN_ATTN_BF16;
+    if (kernel == 0) {
+        if (D == 64) { *v = bf ? variant_of<MhaBF16D64>() : variant_of<MhaF16D64>(); return true; }
+        if (D == 128) { *v = bf ? variant_of<MhaBF16D128>() : variant_of<MhaF16D128>(); return true; }
+    } else {
+        if (D == 64) { *v = bf ? variant_of<GqaBF16D64>() : variant_of<GqaF16D64>(); return true; }
+        if (D == 128) { *v = bf ? variant_of<GqaBF16D128>() : variant_of<GqaF16D128>(); return true; }
+    }
+    return false;
+}
+
+static int tile_tokens(int kernel, int D) {
+    if (kernel == 0) return kNW * kU * (64 / (D / 8));
+    return kNW * kNBLK * 16;
+}
+
+// Workgroups of a variant that fit on one compute unit, and the unit count, cached per device.
+struct DeviceInfo {
+    int cus = 0;
+    int resident[2][2][2] = {};  // [kernel][dtype][D == 128]
+    bool ready = false;
+};
+static DeviceInfo g_dev[64];
+static std::mutex g_dev_mutex;
+
+static int query_device(int kernel, int dtype, int D, int* cus, int* per_cu) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LEAN_ATTN_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    DeviceInfo& di = g_dev[dev];
+    if (!di.ready) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return LEAN_ATTN_ERR_HIP;
+        di.cus = prop.multiProcessorCount;
+        for (int kn = 0; kn < 2; ++kn)
+            for (int dt = 0; dt < 2; ++dt)
+                for (int dd = 0; dd < 2; ++dd) {
+                    Variant v;
+                    pick_variant(kn, dt, dd ? 128 : 64, &v);
+                    int n = 0;
+                    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, v.fn, v.threads, 0) != hipSuccess)
+                        return LEAN_ATTN_ERR_HIP;
+                    di.resident[kn][dt][dd] = n;
+                }
+        di.ready = true;
+    }
+    *cus = di.cus;
+    *per_cu = di.resident[kernel][dtype][D == 128];
+    return LEAN_ATTN_OK;
+}
+
+static int check_shape(int B, int Hq, int Hkv, int D, int dtype, int kv_layout) {
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return LEAN_ATTN_ERR_BAD_SHAPE;
+    if (Hq / Hkv > LEAN_ATTN_MAX_GROUP) return LEAN_ATTN_ERR_BAD_SHAPE;
+    if (B > LEAN_ATTN_MAX_BATCH) return LEAN_ATTN_ERR_BATCH_TOO_LARGE;
+    if (D != 64 && D != 128) return LEAN_ATTN_ERR_UNSUPPORTED;
+    if (dtype != LEAN_ATTN_F16 && dtype != LEAN_ATTN_BF16) return LEAN_ATTN_ERR_UNSUPPORTED;
+    if (kv_layout != LEAN_ATTN_KV_PADDED && kv_layout != LEAN_ATTN_KV_PACKED) return LEAN_ATTN_ERR_UNSUPPORTED;
+    return LEAN_ATTN_OK;
+}
+
+// The host scheduler: per-sequence tile counts, total iterations, grid, spans.
+// O(B) integer work; nothing here touches the device unless the unit count has
+// to be read.
+static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, int dtype, int kv_layout,
+                         const lean_attn_tuning* tn, lean_attn_plan* plan, Sched* sched, SchedTable* table) {
+    if (!seqlens || !plan) return LEAN_ATTN_ERR_NULL_POINTER;
+    int rc = check_shape(B, Hq, Hkv, D, dtype, kv_layout);
+    if (rc != LEAN_ATTN_OK) return rc;
+    lean_attn_tuning t;
+    std::memset(&t, 0, sizeof t);
+    if (tn) t = *tn;
+    if (t.grid < 0 || t.ctas_per_cu < 0 || t.num_cus < 0 || t.kernel < 0 || t.kernel > 2 || t.xcd_remap < 0 ||
+        t.xcd_remap > 2 || t.spin_limit < 0)
+        return LEAN_ATTN_ERR_TUNING;
+    const int T_m = Hq / Hkv;
+    int kernel = T_m == 1 ? 0 : 1;
+    if (t.kernel == 1) {
+        if (T_m != 1) return LEAN_ATTN_ERR_TUNING;
+        kernel = 0;
+    } else if (t.kernel == 2) {
+        kernel = 1;
+    }
+    const int T_n = tile_tokens(kernel, D);
+
+    int64_t iters = 0, toks = 0;
+    for (int b = 0; b < B; ++b) {
+        if (seqlens[b] < 0) return LEAN_ATTN_ERR_SEQLEN;
+        if (table) {
+            table->cu_iters[b] = (int32_t)iters;
+            table->cu_tok[b] = (int32_t)toks;
+        }
+        if ((int64_t)seqlens[b] * D * 2 > INT32_MAX) return LEAN_ATTN_ERR_SEQLEN;  // one slab per buffer descriptor
+        iters += ((int64_t)seqlens[b] + T_n - 1) / T_n;
+        toks += seqlens[b];
+        if (toks > INT32_MAX) return LEAN_ATTN_ERR_SEQLEN;
+    }
+    if (table) {
+        table->cu_iters[B] = (int32_t)iters;
+        table->cu_tok[B] = (int32_t)toks;
+    }
+    const int64_t I = iters * Hkv;
+
+    int cus = t.num_cus, per_cu = t.ctas_per_cu;
+    int64_t resident;
+    if (cus <= 0) {  // read the device: unit count and how many workgroups of this kernel fit per unit
+        int hw_per_cu = 0;
+        rc = query_device(kernel, dtype, D, &cus, &hw_per_cu);
+        if (rc != LEAN_ATTN_OK) return rc;
+        if (hw_per_cu <= 0) return LEAN_ATTN_ERR_HIP;
+        if (per_cu <= 0) per_cu = hw_per_cu < kDefaultCtasPerCu ? hw_per_cu : kDefaultCtasPerCu;
+        if (per_cu > hw_per_cu) per_cu = hw_per_cu;
+        resident = (int64_t)cus * hw_per_cu;
+    } else {
+        if (per_cu <= 0) per_cu = kDefaultCtasPerCu;
+        resident = (int64_t)cus * per_cu;
+    }
+    if (resident > LEAN_ATTN_MAX_GRID) resident = LEAN_ATTN_MAX_GRID;
+    int64_t G = (int64_t)cus * per_cu;
+    if (t.grid > 0) G = t.grid;
+    if (G > resident) G = resident;  // every CTA must be co-resident: hosts wait for peers
+    if (G > I) G = I;
+    if (G < 1) G = 1;
+
+    plan->T_n = T_n;
+    plan->T_m = T_m;
+    plan->num_output_tiles = B * Hkv;
+    plan->grid = (int32_t)G;
+    plan->total_iters = I;
+    plan->iters_per_cta = I / G;
+    plan->extra = (int32_t)(I % G);
+    plan->block_threads = kNW * 64;
+    plan->max_resident = (int32_t)resident;
+    plan->kernel = kernel;
+    if (sched) {
+        sched->B = B;
+        sched->Hkv = Hkv;
+        sched->T_n = T_n;
+        sched->packed = kv_layout == LEAN_ATTN_KV_PACKED;
+        sched->grid = plan->grid;
+        sched->extra = plan->extra;
+        sched->total_iters = I;
+        sched->iters_per_cta = plan->iters_per_cta;
+    }
+    return LEAN_ATTN_OK;
+}
+
+}  // namespace lean
+
+using namespace lean;
+
+extern "C" {
+
+size_t lean_attn_workspace_size(int B, int Hq, int Hkv, int D, int dtype) {
+    if (check_shape(B, Hq, Hkv, D, dtype, LEAN_ATTN_KV_PADDED) != LEAN_ATTN_OK) return 0;
+    return kPartialsOffset + (size_t)kMaxGrid * slot_floats(Hq / Hkv, D) * sizeof(float);
+}
+
+int lean_attn_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!workspace) return LEAN_ATTN_ERR_NULL_POINTER;
+    if (workspace_bytes < kPartialsOffset || ((uintptr_t)workspace & 255) != 0) return LEAN_ATTN_ERR_WORKSPACE;
+    const int n = (int)(kPartialsOffset / 4);
+    hipLaunchKernelGGL(lean_workspace_clear_kernel, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)hip_stream,
+                       (uint32_t*)workspace, n);
+    return hipGetLastError() == hipSuccess ? LEAN_ATTN_OK : LEAN_ATTN_ERR_HIP;
+}
+
+int lean_attn_workspace_status(void* workspace, void* hip_stream) {
+    if (!workspace) return LEAN_ATTN_ERR_NULL_POINTER;
+    uint32_t word = 0;
+    if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return LEAN_ATTN_ERR_HIP;
+    if (hipMemcpy(&word, workspace, 4, hipMemcpyDeviceToHost) != hipSuccess) return LEAN_ATTN_ERR_HIP;
+    if (word != 0) {
+        // A peer that arrived after its host gave up left its flag set: clear them all.
+        const int n = (int)(kPartialsOffset / 4);
+        hipLaunchKernelGGL(lean_workspace_clear_kernel, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)hip_stream,
+                           (uint32_t*)workspace, n);
+        if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return LEAN_ATTN_ERR_HIP;
+        return LEAN_ATTN_ERR_PEER_TIMEOUT;
+    }
+    return LEAN_ATTN_OK;
+}
+
+int lean_attn_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, int dtype, int kv_layout,
+                       const lean_attn_tuning* tuning, lean_attn_plan* plan) {
+    return make_schedule(seqlens, B, Hq, Hkv, D, dtype, kv_layout, tuning, plan, nullptr, nullptr);
+}
+
+int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, int Hkv, int kv_layout, int g,
+                   int64_t* segments, int max_segments) {
+    if (!plan || !seqlens || !segments) return LEAN_ATTN_ERR_NULL_POINTER;
+    if (B <= 0 || B > LEAN_ATTN_MAX_BATCH || Hkv <= 0 || plan->T_n <= 0) return LEAN_ATTN_ERR_BAD_SHAPE;
+    if (g < 0 || g >= plan->grid) return LEAN_ATTN_ERR_TUNING;
+    Sched s;
+    SchedTable t;
+    int64_t iters = 0, toks = 0;
+    for (int b = 0; b < B; ++b) {
+        if (seqlens[b] < 0) return LEAN_ATTN_ERR_SEQLEN;
+        t.cu_iters[b] = (int32_t)iters;
+        t.cu_tok[b] = (int32_t)toks;
+        iters += ((int64_t)seqlens[b] + plan->T_n - 1) / plan->T_n;
+        toks += seqlens[b];
+    }
+    t.cu_iters[B] = (int32_t)iters;
+    t.cu_tok[B] = (int32_t)toks;
+    s.B = B;
+    s.Hkv = Hkv;
+    s.T_n = plan->T_n;
+    s.packed = kv_layout == LEAN_ATTN_KV_PACKED;
+    s.grid = plan->grid;
+    s.extra = plan->extra;
+    s.total_iters = plan->total_iters;
+    s.iters_per_cta = plan->iters_per_cta;
+    if (iters * Hkv != plan->total_iters) return LEAN_ATTN_ERR_BAD_SHAPE;
+    int64_t it, end;
+    span_of(s, g, &it, &end);
+    int n = 0;
+    while (it < end) {
+        const Segment sg = locate(s, t, it, end);
+        if (n < max_segments) {
+            int64_t* rec = segments + 8 * (int64_t)n;
+            rec[0] = sg.tile_idx;
+            rec[1] = sg.b;
+            rec[2] = sg.h;
+            rec[3] = sg.local_iter;
+            rec[4] = sg.local_iter_end;
+            rec[5] = sg.host;
+            rec[6] = sg.finishing;
+            rec[7] = sg.last_cta;
+        }
+        ++n;
+        it = sg.tile_iter_end;
+    }
+    return n;
+}
+
+int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache, const int32_t* seqlens, float* out,
+                     float* lse, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv, int D,
+                     int kv_layout, int64_t kv_seq_stride, float scale, int dtype, const lean_attn_tuning* tuning,
+                     void* hip_stream) {
+    if (!q || !k_cache || !v_cache || !seqlens || !out || !workspace) return LEAN_ATTN_ERR_NULL_POINTER;
+    int rc = check_shape(B, Hq, Hkv, D, dtype, kv_layout);
+    if (rc != LEAN_ATTN_OK) return rc;
+    if ((((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache) & 15) != 0) return LEAN_ATTN_ERR_BAD_SHAPE;
+    if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < lean_attn_workspace_size(B, Hq, Hkv, D, dtype))
+        return LEAN_ATTN_ERR_WORKSPACE;
+
+    lean_attn_plan plan;
+    DecodeArgs a;
+    rc = make_schedule(seqlens, B, Hq, Hkv, D, dtype, kv_layout, tuning, &plan, &a.sched, &a.table);
+    if (rc != LEAN_ATTN_OK) return rc;
+    int32_t longest = 0, has_empty = 0;
+    for (int b = 0; b < B; ++b) {
+        if (seqlens[b] > longest) longest = seqlens[b];
+        if (seqlens[b] == 0) has_empty = 1;
+    }
+    if (kv_layout == LEAN_ATTN_KV_PADDED && kv_seq_stride < longest) return LEAN_ATTN_ERR_SEQLEN;
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (plan.total_iters == 0) {  // every sequence is empty
+        const int64_t rows = (int64_t)B * Hq;
+        hipLaunchKernelGGL(lean_zero_rows_kernel, dim3((unsigned)((rows * D + 255) / 256)), dim3(256), 0, stream, out,
+                           lse, rows, D);
+        return hipGetLastError() == hipSuccess ? LEAN_ATTN_OK : LEAN_ATTN_ERR_HIP;
+    }
+
+    Variant var;
+    if (!pick_variant(plan.kernel, dtype, D, &var)) return LEAN_ATTN_ERR_UNSUPPORTED;
+
+    a.q = (const uint16_t*)q;
+    a.k = (const uint16_t*)k_cache;
+    a.v = (const uint16_t*)v_cache;
+    a.out = out;
+    a.lse = lse;
+    a.status = (uint32_t*)workspace;
+    a.flags = (uint32_t*)((char*)workspace + kFlagsOffset);
+    a.partials = (float*)((char*)workspace + kPartialsOffset);
+    a.kv_seq_stride = kv_seq_stride;
+    a.total_rows = a.table.cu_tok[B];
+    a.Hq = Hq;
+    a.T_m = plan.T_m;
+    a.slot = slot_floats(plan.T_m, D);
+    a.xcd_remap = (tuning && tuning->xcd_remap == 2) ? 1 : 0;
+    a.spin_limit = (tuning && tuning->spin_limit > 0) ? tuning->spin_limit : (1 << 22);
+    a.has_empty = has_empty;
+    a.scale_log2e = scale * 1.4426950408889634f;
+
+    void* params[] = {&a};
+    if (hipLaunchKernel(var.fn, dim3(plan.grid), dim3(var.threads), params, 0, stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return LEAN_ATTN_ERR_HIP;
+    }
+    return LEAN_ATTN_OK;
+}
+
+int lean_attn_read_probe(const void* buf, size_t bytes, void* sink, int grid, void* hip_stream) {
+    if (!buf || !sink) return LEAN_ATTN_ERR_NULL_POINTER;
+    if (bytes == 0 || (bytes & 15) != 0 || ((uintptr_t)buf & 15) != 0 || grid <= 0 || grid > 65535)
+        return LEAN_ATTN_ERR_BAD_SHAPE;
+    hipLaunchKernelGGL(lean_read_probe_kernel, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream, (const uint4*)buf,
+                       (int64_t)(bytes / 16), (uint32_t*)sink);
+    return hipGetLastError() == hipSuccess ? LEAN_ATTN_OK : LEAN_ATTN_ERR_HIP;
+}
+
+const char* lean_attn_strerror(int status) {
+    switch (status) {
+        case LEAN_ATTN_OK: return "ok";
+        case LEAN_ATTN_ERR_NULL_POINTER: return "a required pointer is null";
+        case LEAN_ATTN_ERR_BAD_SHAPE: return "bad shape: B, Hq, Hkv must be positive, Hq a multiple of Hkv with group <= 16, 16-byte aligned tensors";
+        case LEAN_ATTN_ERR_UNSUPPORTED: return "unsupported head dim (64, 128), dtype (f16, bf16) or layout";
+        case LEAN_ATTN_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or smaller than lean_attn_workspace_size";
+        case LEAN_ATTN_ERR_SEQLEN: return "negative sequence length, padded stride below the longest sequence, or more than 2^31 tokens";
+        case LEAN_ATTN_ERR_BATCH_TOO_LARGE: return "batch larger than LEAN_ATTN_MAX_BATCH";
+        case LEAN_ATTN_ERR_HIP: return "a HIP runtime call failed";
+        case LEAN_ATTN_ERR_TUNING: return "tuning field out of range";
+        case LEAN_ATTN_ERR_PEER_TIMEOUT: return "a host workgroup gave up waiting for a peer's partial";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

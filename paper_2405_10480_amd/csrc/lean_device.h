@@ -1,0 +1,153 @@
+// Device-side building blocks shared by the two decode cores: kernel argument
+// block, workspace layout, 16-bit element handling, cross-lane reductions and
+// the arrival-flag protocol of Algorithm 2 (StorePartials / Signal / Wait).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lean_sched.h"
+
+namespace lean {
+
+constexpr int kDtF16 = 0;
+constexpr int kDtBF16 = 1;
+constexpr int kMaxGrid = 2048;
+
+// Workspace layout (bytes): [0,256) status word, [256, 256+4*kMaxGrid) flags,
+// then kMaxGrid partial slots of slot_floats floats: O~[T_m][D], m[T_m], l[T_m].
+constexpr size_t kFlagsOffset = 256;
+constexpr size_t kPartialsOffset = kFlagsOffset + 4 * (size_t)kMaxGrid;
+
+inline __host__ __device__ int slot_floats(int T_m, int D) {
+    const int n = T_m * (D + 2);
+    return (n + 63) & ~63;  // 256-byte slots
+}
+
+struct DecodeArgs {
+    const uint16_t* q;
+    const uint16_t* k;
+    const uint16_t* v;
+    float* out;
+    float* lse;            // may be null
+    uint32_t* status;      // workspace + 0
+    uint32_t* flags;       // workspace + kFlagsOffset
+    float* partials;       // workspace + kPartialsOffset
+    int64_t kv_seq_stride; // PADDED: rows between (b,h) slabs
+    int64_t total_rows;    // PACKED: sum of N_b
+    int32_t Hq;
+    int32_t T_m;           // Hq / Hkv
+    int32_t slot;          // floats per partial slot
+    int32_t xcd_remap;
+    int32_t spin_limit;
+    int32_t has_empty;     // some N_b == 0: those output rows must be zeroed
+    float scale_log2e;     // scale * log2(e): scores live in the base-2 domain
+    Sched sched;
+    SchedTable table;
+};
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// The two 16-bit elements packed in one dword, widened to fp32 (low half first).
+template <int DT>
+__device__ __forceinline__ void widen2(uint32_t u, float& lo, float& hi) {
+    if constexpr (DT == kDtBF16) {
+        lo = as_f32(u << 16);
+        hi = as_f32(u & 0xffff0000u);
+    } else {
+        const f16x2 h = __builtin_bit_cast(f16x2, u);
+        lo = (float)h.x;
+        hi = (float)h.y;
+    }
+}
+
+// acc + a.lo*b.lo + a.hi*b.hi on packed 16-bit pairs, fp32 accumulate.
+template <int DT>
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float acc) {
+    if constexpr (DT == kDtBF16) {
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), acc,
+                                               false);
+    } else {
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, a), __builtin_bit_cast(f16x2, b), acc, false);
+    }
+}
+
+// ---- K/V streaming through buffer loads ---------------------------------------------------
+// One buffer descriptor per (sequence, KV head) slab with num_records = N_b * D * 2
+// bytes: a 16-byte load whose offset falls past the slab returns zeros instead of
+// touching memory, so the ragged tail tile needs no address clamping.  The whole
+// offset goes in the VGPR/immediate part, which is what the range check covers.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+using buffer_rsrc = __amdgpu_buffer_rsrc_t;
+
+__device__ __forceinline__ buffer_rsrc make_slab(const uint16_t* base, uint32_t bytes) {
+    // flags: raw 32-bit data format, the untyped-buffer setting for gfx9-family descriptors
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ u32x4 slab_load16(buffer_rsrc r, uint32_t byte_off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+}
+__device__ __forceinline__ u32x2 slab_load8(buffer_rsrc r, uint32_t byte_off) {
+    return __builtin_amdgcn_raw_buffer_load_b64(r, (int)byte_off, 0, 0);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over each aligned group of LANES (8 or 16) consecutive lanes; every lane
+// of the group ends with the total.  Butterfly on DPP lane permutations:
+// quad_perm[1,0,3,2], quad_perm[2,3,0,1], row_half_mirror, row_mirror.
+template <int LANES>
+__device__ __forceinline__ float group_allreduce_sum(float x) {
+    static_assert(LANES == 8 || LANES == 16, "row of 8 or 16 lanes");
+    x += dpp_move<0xB1>(x);
+    x += dpp_move<0x4E>(x);
+    x += dpp_move<0x141>(x);
+    if constexpr (LANES == 16) x += dpp_move<0x140>(x);
+    return x;
+}
+
+__device__ __forceinline__ float xor_shuffle(float x, int lane_mask) { return __shfl_xor(x, lane_mask, 64); }
+
+// ---- Algorithm 2: Signal / Wait on flags in global memory -------------------------------
+// Signal: every thread of the workgroup has stored its share of the partial;
+// a device-scope release makes those stores visible before the flag.
+__device__ __forceinline__ void signal_arrival(uint32_t* flag) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_store(flag, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Wait: thread 0 polls the flag (bounded), then the whole workgroup acquires at
+// device scope so that its following loads observe the peer's partial.  The
+// consumer clears the flag: each flag has exactly one consumer per launch, so
+// the workspace is clean again when the kernel ends.
+__device__ __forceinline__ void wait_arrival(uint32_t* flag, uint32_t* status, int spin_limit) {
+    if (threadIdx.x == 0) {
+        int spins = 0;
+        while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+            __builtin_amdgcn_s_sleep(8);
+            if (++spins >= spin_limit) {  // peer never arrived: report, do not hang
+                __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+        }
+        __hip_atomic_store(flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+}
+
+}  // namespace lean

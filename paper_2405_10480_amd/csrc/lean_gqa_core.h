@@ -1,0 +1,244 @@
+// LeanTile inner loop (Algorithm 1) for a group of T_m <= 16 query heads that
+// share one KV head.  The group forms the T_m rows of Q_f, so each K/V tile is
+// read once for the whole group and QK^T / PV are small dense contractions:
+// they run on the matrix cores (v_mfma_f32_16x16x16 in bf16 or f16), with the
+// online softmax in fp32 on the VALU.
+//
+// Per wave and per block of 16 tokens (indices below are within the block):
+//
+//   S^T[16 tok x 16 head] = K_blk * Q^T         A = K (m: token, k: head dim), B = Q^T
+//     lane (r = lane%16, g = lane/16) supplies token 4*(r%4) + r/4, so that the
+//     accumulator register i of lane (h, g) is the score of token 4*i + g for
+//     head h: exactly the B-operand layout (k = 4*g + j <-> token 4*j + g) of
+//
+//   O^T[D x 16 head] += V_blk^T * P^T            A = V^T (m: head dim, k: token), B = P^T
+//     lane (m = lane%16, g) loads, for j = 0..3, the D/16 head-dim elements
+//     [m*D/16, (m+1)*D/16) of token 4*j + g: the four loads of a wave are fully
+//     coalesced (one contiguous KiB each at D = 128), and the 4-token x D/16
+//     sub-block a lane holds is transposed in registers (v_perm_b32) into the
+//     D/16 A operands.  Accumulator e, register i of lane (h, g) is
+//     O[h][ (D/16)*(4*g + i) + e ].
+//
+// P is split into a high and a low 16-bit part (P = P_hi + P_lo, two MFMAs per
+// operand) so that rounding P to the input precision never limits accuracy.
+// K and V go from global memory straight to the MFMA operand registers; LDS is
+// used only to hand the per-wave partials to the workgroup epilogue.
+#pragma once
+#include "lean_device.h"
+
+namespace lean {
+
+template <int DT>
+__device__ __forceinline__ f32x4 mfma16(uint2 a, uint2 b, f32x4 c) {
+    if constexpr (DT == kDtBF16) {
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a), __builtin_bit_cast(s16x4, b),
+                                                        c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, a), __builtin_bit_cast(f16x4, b), c,
+                                                    0, 0, 0);
+    }
+}
+
+// Split two non-negative fp32 weights into packed 16-bit high parts and packed
+// 16-bit remainders: p = hi + lo up to 2^-16 (bf16, truncation) or 2^-21 (f16) relative.
+template <int DT>
+__device__ __forceinline__ void split_pair(float p0, float p1, uint32_t& hi, uint32_t& lo) {
+    if constexpr (DT == kDtBF16) {
+        hi = __builtin_amdgcn_perm(as_u32(p1), as_u32(p0), 0x07060302u);
+        const float r0 = p0 - as_f32(as_u32(p0) & 0xffff0000u);
+        const float r1 = p1 - as_f32(as_u32(p1) & 0xffff0000u);
+        lo = __builtin_amdgcn_perm(as_u32(r1), as_u32(r0), 0x07060302u);
+    } else {
+        const f16x2 h = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(p0, p1));
+        hi = __builtin_bit_cast(uint32_t, h);
+        const f16x2 r = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(p0 - (float)h.x, p1 - (float)h.y));
+        lo = __builtin_bit_cast(uint32_t, r);
+    }
+}
+
+template <int D>
+struct VVec;
+template <>
+struct VVec<128> {
+    using type = u32x4;
+};
+template <>
+struct VVec<64> {
+    using type = u32x2;
+};
+
+template <int D>
+__device__ __forceinline__ uint32_t vdword(const typename VVec<D>::type& v, int i) {
+    return v[i];
+}
+
+template <int DT, int D, int NBLK, int NW>
+struct GqaCore {
+    static constexpr int kD = D;
+    static constexpr int kTn = NW * NBLK * 16;  // LeanTile
+    static constexpr int kCH = NBLK * 16;       // tokens per wave per step
+    static constexpr int kThreads = NW * 64;
+    static constexpr int kTmMax = 16;
+    static constexpr int kStreams = NW;
+    static constexpr int kMinWavesPerSimd = 2;
+    static constexpr int kKC = D / 32;          // 16-byte K pieces per lane per block
+    static constexpr int kEV = D / 16;          // head-dim elements per lane per token (V side)
+    static constexpr int kVW = kEV / 2;         // dwords per lane per token (V side)
+    static_assert(D == 64 || D == 128, "head dim");
+    using vvec = typename VVec<D>::type;
+
+    struct Smem {
+        float o[kStreams][kTmMax][D];
+        float m[kStreams][kTmMax];
+        float l[kStreams][kTmMax];
+    };
+
+    __device__ static void run(const DecodeArgs& a, const Segment& sg, Smem& sm) {
+        const int lane = threadIdx.x & 63;
+        const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int r = lane & 15;   // A row / B column index of the lane
+        const int g = lane >> 4;   // k-group of the lane
+        const int n_ctx = sg.n_ctx;
+        const int T_m = a.T_m;
+
+        const int64_t row0 = a.sched.packed
+                                 ? (int64_t)sg.h * a.total_rows + a.table.cu_tok[sg.b]
+                                 : ((int64_t)sg.b * a.sched.Hkv + sg.h) * a.kv_seq_stride;
+        constexpr uint32_t kRowBytes = D * 2;
+        const uint32_t slab_bytes = (uint32_t)n_ctx * kRowBytes;
+        const buffer_rsrc k_slab = make_slab(a.k + row0 * D, slab_bytes);
+        const buffer_rsrc v_slab = make_slab(a.v + row0 * D, slab_bytes);
+        const int k_tok = 4 * (r & 3) + (r >> 2);  // token (within a block) this lane feeds as A row r
+        const uint32_t k_lane_off = (uint32_t)(w * kCH + k_tok) * kRowBytes + (uint32_t)g * 16u;
+        const uint32_t v_lane_off = (uint32_t)(w * kCH + g) * kRowBytes + (uint32_t)r * (kEV * 2u);
+
+        // Q^T as B operands: lane (h = r, g) holds Q[h][32*c2 + 8*g .. +8), zero rows past T_m.
+        u32x4 qb[kKC];
+#pragma unroll
+        for (int c2 = 0; c2 < kKC; ++c2) qb[c2] = u32x4{0u, 0u, 0u, 0u};
+        if (r < T_m) {
+            const u32x4* qp =
+                reinterpret_cast<const u32x4*>(a.q + ((int64_t)sg.b * a.Hq + (int64_t)sg.h * T_m + r) * D) + g;
+#pragma unroll
+            for (int c2 = 0; c2 < kKC; ++c2) qb[c2] = qp[4 * c2];
+        }
+
+        float m_run = -INFINITY;  // head r, shared by the four k-group lanes
+        float l_run = 0.f;        // this lane's share of l (tokens 4*i + g); summed over g at the end
+        f32x4 acc[kEV];
+#pragma unroll
+        for (int e = 0; e < kEV; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        u32x4 kA[NBLK][kKC], kB[NBLK][kKC];
+        vvec vA[NBLK][4], vB[NBLK][4];
+
+        // K: 16-byte pieces, row-strided (lane r -> its token, lane group g -> 16 B of each
+        // 64-byte quarter-row).  V: per j one fully coalesced wave-wide load of 4 rows.
+        auto load = [&](u32x4(&kb)[NBLK][kKC], vvec(&vb)[NBLK][4], int step) {
+            const uint32_t koff = k_lane_off + (uint32_t)step * (kTn * kRowBytes);
+            const uint32_t voff = v_lane_off + (uint32_t)step * (kTn * kRowBytes);
+#pragma unroll
+            for (int blk = 0; blk < NBLK; ++blk) {
+#pragma unroll
+                for (int c2 = 0; c2 < kKC; ++c2)
+                    kb[blk][c2] = slab_load16(k_slab, koff + (uint32_t)(blk * 16) * kRowBytes + c2 * 64u);
+            }
+#pragma unroll
+            for (int blk = 0; blk < NBLK; ++blk) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t o = voff + (uint32_t)(blk * 16 + 4 * j) * kRowBytes;
+                    if constexpr (D == 128) vb[blk][j] = slab_load16(v_slab, o);
+                    else vb[blk][j] = slab_load8(v_slab, o);
+                }
+            }
+        };
+
+        auto compute = [&](const u32x4(&kb)[NBLK][kKC], const vvec(&vb)[NBLK][4], int step) {
+            const int base = step * kTn + w * kCH;
+            f32x4 s[NBLK];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int blk = 0; blk < NBLK; ++blk) {
+                f32x4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int c2 = 0; c2 < kKC; ++c2) {
+                    c = mfma16<DT>(make_uint2(kb[blk][c2].x, kb[blk][c2].y), make_uint2(qb[c2].x, qb[c2].y), c);
+                    c = mfma16<DT>(make_uint2(kb[blk][c2].z, kb[blk][c2].w), make_uint2(qb[c2].z, qb[c2].w), c);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float x = c[i] * a.scale_log2e;
+                    if (base + blk * 16 + 4 * i + g >= n_ctx) x = -INFINITY;  // masked tail tokens
+                    c[i] = x;
+                    mx = fmaxf(mx, x);
+                }
+                s[blk] = c;
+            }
+            mx = fmaxf(mx, xor_shuffle(mx, 16));
+            mx = fmaxf(mx, xor_shuffle(mx, 32));
+            const float m_new = fmaxf(m_run, mx);
+            const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = fast_exp2(m_run - m_ref);
+            m_run = m_new;
+            float psum = 0.f;
+            uint2 p_hi[NBLK], p_lo[NBLK];
+#pragma unroll
+            for (int blk = 0; blk < NBLK; ++blk) {
+                float p[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    p[i] = fast_exp2(s[blk][i] - m_ref);
+                    psum += p[i];
+                }
+                split_pair<DT>(p[0], p[1], p_hi[blk].x, p_lo[blk].x);
+                split_pair<DT>(p[2], p[3], p_hi[blk].y, p_lo[blk].y);
+            }
+            l_run = l_run * alpha + psum;
+            if (__any(alpha != 1.f)) {  // the running max moved for some head of this wave
+#pragma unroll
+                for (int e = 0; e < kEV; ++e) acc[e] *= alpha;
+            }
+#pragma unroll
+            for (int blk = 0; blk < NBLK; ++blk) {
+#pragma unroll
+                for (int e = 0; e < kEV; ++e) {
+                    const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                    uint2 va;
+                    va.x = __builtin_amdgcn_perm(vdword<D>(vb[blk][1], e >> 1), vdword<D>(vb[blk][0], e >> 1), sel);
+                    va.y = __builtin_amdgcn_perm(vdword<D>(vb[blk][3], e >> 1), vdword<D>(vb[blk][2], e >> 1), sel);
+                    acc[e] = mfma16<DT>(va, p_hi[blk], acc[e]);
+                    acc[e] = mfma16<DT>(va, p_lo[blk], acc[e]);
+                }
+            }
+        };
+
+        const int it_end = sg.local_iter_end;
+        const int it_last = it_end - 1;
+        int it = sg.local_iter;
+        load(kA, vA, it);
+        while (it < it_end) {
+            load(kB, vB, min(it + 1, it_last));
+            compute(kA, vA, it);
+            load(kA, vA, min(it + 2, it_last));
+            if (it + 1 < it_end) compute(kB, vB, it + 1);
+            it += 2;
+        }
+
+        // l over the four k-group lanes of each head; m is already common to them.
+        l_run += xor_shuffle(l_run, 16);
+        l_run += xor_shuffle(l_run, 32);
+#pragma unroll
+        for (int e = 0; e < kEV; ++e) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sm.o[w][r][kEV * (4 * g + i) + e] = acc[e][i];
+        }
+        if (g == 0) {
+            sm.m[w][r] = m_run;
+            sm.l[w][r] = l_run;
+        }
+        __syncthreads();
+    }
+};
+
+}  // namespace lean

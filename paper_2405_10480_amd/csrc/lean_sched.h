@@ -1,0 +1,113 @@
+// Stream-K schedule of LeanAttention (Section 4.3; first lines and loop header
+// of Algorithm 2), shared by the host scheduler and the device span walk so
+// that both run literally the same index arithmetic.
+//
+// Output tile  = one (sequence b, KV head h) pair; it owns C_n[b] = ceil(N_b / T_n)
+//                LeanTile iterations.
+// Linearization: PADDED cache  b -> h -> context   (iter = Hkv*cuC[b] + h*C_n[b] + local)
+//                PACKED cache  h -> b -> context   (iter = h*cuC[B] + cuC[b] + local)
+//                (the paper's "batch -> heads -> context" and, for ragged
+//                batches, "Heads -> TotalContextLength"; the result does not
+//                depend on the order, each follows its layout in memory).
+// Spans:         CTA g owns [g*q + min(g, r), +q + (g < r)) with q = I / G, r = I mod G
+//                (the paper divides I by G and is silent on a remainder).
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define LEAN_HD __host__ __device__ inline
+#else
+#define LEAN_HD inline
+#endif
+
+namespace lean {
+
+constexpr int kMaxBatch = 256;
+
+// Prefix sums over the batch; travels to the kernel by value as kernel arguments.
+struct SchedTable {
+    int32_t cu_iters[kMaxBatch + 1];  // cuC[b] = sum_{b'<b} ceil(N_b' / T_n)
+    int32_t cu_tok[kMaxBatch + 1];    // sum_{b'<b} N_b'
+};
+
+struct Sched {
+    int32_t B;
+    int32_t Hkv;
+    int32_t T_n;
+    int32_t packed;         // 0: PADDED order b->h->t, 1: PACKED order h->b->t
+    int32_t grid;           // G
+    int32_t extra;          // I mod G
+    int64_t total_iters;    // I
+    int64_t iters_per_cta;  // I / G
+};
+
+// One output-tile segment of a CTA's span (one trip of Algorithm 2's loop).
+struct Segment {
+    int32_t b, h;
+    int32_t tile_idx;         // PADDED: b*Hkv + h, PACKED: h*B + b
+    int32_t local_iter;       // first LeanTile iteration inside the tile
+    int32_t local_iter_end;   // one past the last
+    int32_t n_ctx;            // N_b
+    int32_t host;             // this CTA computed the tile's first iteration
+    int32_t finishing;        // this CTA's span reaches the tile's end
+    int32_t last_cta;         // last peer contributing to the tile (valid when host && !finishing)
+    int64_t tile_iter_end;    // global iteration index one past the tile
+};
+
+LEAN_HD void span_of(const Sched& s, int g, int64_t* begin, int64_t* end) {
+    const int64_t lo = (int64_t)g * s.iters_per_cta + (g < s.extra ? g : s.extra);
+    *begin = lo;
+    *end = lo + s.iters_per_cta + (g < s.extra ? 1 : 0);
+}
+
+// The CTA whose span holds global iteration `it`.
+LEAN_HD int cta_of_iter(const Sched& s, int64_t it) {
+    const int64_t fat = (int64_t)s.extra * (s.iters_per_cta + 1);
+    if (it < fat) return (int)(it / (s.iters_per_cta + 1));
+    return s.extra + (int)((it - fat) / s.iters_per_cta);
+}
+
+// Largest b in [0, B) with cu_iters[b] <= key (key < cu_iters[B]); skips empty sequences.
+LEAN_HD int find_sequence(const SchedTable& t, int B, int32_t key) {
+    int lo = 0, hi = B;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (t.cu_iters[mid] <= key) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Segment of the tile containing global iteration `it`, clipped to the CTA's span end.
+LEAN_HD Segment locate(const Sched& s, const SchedTable& t, int64_t it, int64_t cta_end) {
+    Segment sg;
+    int64_t tile_iter;  // global index of the tile's first iteration
+    int32_t c_n;
+    if (s.packed) {
+        const int64_t per_head = t.cu_iters[s.B];
+        sg.h = (int32_t)(it / per_head);
+        const int32_t key = (int32_t)(it - (int64_t)sg.h * per_head);
+        sg.b = find_sequence(t, s.B, key);
+        c_n = t.cu_iters[sg.b + 1] - t.cu_iters[sg.b];
+        tile_iter = (int64_t)sg.h * per_head + t.cu_iters[sg.b];
+        sg.tile_idx = sg.h * s.B + sg.b;
+    } else {
+        const int32_t key = (int32_t)(it / s.Hkv);
+        sg.b = find_sequence(t, s.B, key);
+        c_n = t.cu_iters[sg.b + 1] - t.cu_iters[sg.b];
+        const int64_t seq_iter = (int64_t)s.Hkv * t.cu_iters[sg.b];
+        sg.h = (int32_t)((it - seq_iter) / c_n);
+        tile_iter = seq_iter + (int64_t)sg.h * c_n;
+        sg.tile_idx = sg.b * s.Hkv + sg.h;
+    }
+    sg.n_ctx = t.cu_tok[sg.b + 1] - t.cu_tok[sg.b];
+    sg.tile_iter_end = tile_iter + c_n;
+    sg.local_iter = (int32_t)(it - tile_iter);
+    const int64_t stop = sg.tile_iter_end < cta_end ? sg.tile_iter_end : cta_end;
+    sg.local_iter_end = (int32_t)(stop - tile_iter);
+    sg.host = it == tile_iter;
+    sg.finishing = cta_end >= sg.tile_iter_end;
+    sg.last_cta = (sg.host && !sg.finishing) ? cta_of_iter(s, sg.tile_iter_end - 1) : -1;
+    return sg;
+}
+
+}  // namespace lean

@@ -1,0 +1,180 @@
+"""Host logic of the HIP library, run without a GPU: the stream-K scheduler and
+span walk (the same code the kernel executes), argument checking, and the
+exported symbols of the C ABI.  No compute entry point is called here."""
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2405_10480_amd as la
+from oracle import lean_alg2
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _plan(seqlens, Hq, Hkv, D, dtype, layout, **kw):
+    return la.lean_attn_schedule(seqlens, Hq, Hkv, D, dtype, layout, la.Tuning(**kw))
+
+
+def test_library_exports_every_declared_symbol():
+    import ctypes
+
+    header = open(os.path.join(ROOT, "include", "lean_attn.h")).read()
+    names = set(re.findall(r"\b(lean_attn_[a-z_]+)\s*\(", header))
+    assert {"lean_attn_decode", "lean_attn_workspace_size", "lean_attn_schedule", "lean_attn_walk",
+            "lean_attn_workspace_init", "lean_attn_workspace_status", "lean_attn_read_probe",
+            "lean_attn_strerror"} <= names
+    lib = ctypes.CDLL(la.library_path())
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in lean_attn.h but not exported"
+
+
+def test_grid_is_units_times_residency_and_spans_are_equal():
+    # the paper's own example: 108 units x 2 CTAs per unit = 216 (Section 4.3)
+    p = _plan([65536] * 4, 32, 32, 64, la.F16, la.KV_PADDED, num_cus=108, ctas_per_cu=2)
+    assert p.T_n == 256 and p.grid == 216 and p.T_m == 1 and p.kernel == 0
+    assert p.total_iters == 4 * 32 * 256
+    assert p.iters_per_cta == p.total_iters // 216 and p.extra == p.total_iters % 216
+    # MI355X: 256 units
+    p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2)
+    assert (p.T_n, p.grid, p.total_iters, p.iters_per_cta, p.extra) == (128, 512, 16384, 32, 0)
+    # never more CTAs than iterations
+    p = _plan([100], 2, 2, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2)
+    assert p.total_iters == 2 and p.grid == 2
+    # a forced grid is honoured but clipped to what is co-resident
+    p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2, grid=7)
+    assert p.grid == 7 and p.extra == 16384 % 7
+    p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=4, ctas_per_cu=2, grid=1000)
+    assert p.grid == 8
+    # query groups use the MFMA kernel, one output tile per KV head
+    p = _plan([262144], 64, 8, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2)
+    assert p.kernel == 1 and p.T_m == 8 and p.num_output_tiles == 8
+    assert p.total_iters == 8 * math.ceil(262144 / p.T_n)
+
+
+@pytest.mark.parametrize("G", [1, 2, 5, 13, 64, 10_000])
+def test_walk_matches_the_step_by_step_emulation_of_algorithm_2(G):
+    Hkv, D = 3, 128
+    seqlens = [700, 1, 0, 257, 3000]
+    p = _plan(seqlens, Hkv, Hkv, D, la.BF16, la.KV_PADDED, num_cus=G, ctas_per_cu=1, grid=G)
+    trace = []
+    r = np.random.default_rng(0)
+    nmax = max(seqlens)
+    q = r.normal(size=(len(seqlens), Hkv, 2))
+    kv = r.normal(size=(len(seqlens), Hkv, nmax, 2))
+    lean_alg2.lean_attention(q, kv, kv, seqlens, Hkv=Hkv, T_n=p.T_n, G=G, scale=1.0, trace=trace)
+    want = {}
+    for t in trace:
+        want.setdefault(t["cta"], []).append(t)
+    assert p.grid == len(lean_alg2.spans(p.total_iters, G))
+    for g in range(p.grid):
+        got = la.lean_attn_walk(p, seqlens, Hkv, la.KV_PADDED, g)
+        ref = sorted(want[g], key=lambda t: (t["b"], t["h"]))
+        assert len(got) == len(ref)
+        for a, b in zip(got, ref):
+            assert (a["b"], a["h"], a["local_iter"], a["local_iter_end"], bool(a["host"]), bool(a["finishing"])) == \
+                   (b["b"], b["h"], b["local_iter"], b["local_iter_end"], b["host"], b["finishing"])
+
+
+def _check_invariants(seqlens, Hkv, layout, p):
+    """Coverage, one host per tile, at most one published partial per CTA, exact peer ranges."""
+    C = [math.ceil(n / p.T_n) for n in seqlens]
+    covered = {}
+    hosts = {}
+    contributors = {}
+    for g in range(p.grid):
+        segs = la.lean_attn_walk(p, seqlens, Hkv, layout, g)
+        assert segs, "every CTA owns at least one iteration"
+        n_iters = sum(s["local_iter_end"] - s["local_iter"] for s in segs)
+        assert n_iters == p.iters_per_cta + (1 if g < p.extra else 0)
+        for i, s in enumerate(segs):
+            key = (s["b"], s["h"])
+            assert 0 <= s["local_iter"] < s["local_iter_end"] <= C[s["b"]]
+            covered.setdefault(key, []).append((s["local_iter"], s["local_iter_end"]))
+            contributors.setdefault(key, []).append(g)
+            if s["host"]:
+                assert s["local_iter"] == 0
+                hosts[key] = (g, s)
+            else:
+                assert i == 0, "only a CTA's first segment can start mid-tile: one workspace slot per CTA"
+            assert bool(s["finishing"]) == (s["local_iter_end"] == C[s["b"]])
+            expect_idx = s["b"] * Hkv + s["h"] if layout == la.KV_PADDED else s["h"] * len(seqlens) + s["b"]
+            assert s["tile_idx"] == expect_idx
+    for b, n in enumerate(seqlens):
+        for h in range(Hkv):
+            if C[b] == 0:
+                assert (b, h) not in covered
+                continue
+            pieces = sorted(covered[(b, h)])
+            assert pieces[0][0] == 0 and pieces[-1][1] == C[b]
+            assert all(x[1] == y[0] for x, y in zip(pieces, pieces[1:]))
+            g, s = hosts[(b, h)]
+            peers = sorted(contributors[(b, h)])
+            assert peers[0] == g and peers == list(range(g, peers[-1] + 1))
+            if not s["finishing"]:
+                assert s["last_cta"] == peers[-1]
+            else:
+                assert len(peers) == 1 and s["last_cta"] == -1
+
+
+@pytest.mark.parametrize("layout", [la.KV_PADDED, la.KV_PACKED])
+@pytest.mark.parametrize("G", [1, 3, 8, 61, 512])
+def test_span_invariants_ragged(layout, G):
+    seqlens = [1024, 131072, 5000, 0, 77, 128, 129, 40000]
+    p = _plan(seqlens, 4, 4, 128, la.BF16, layout, num_cus=G, ctas_per_cu=1, grid=G)
+    _check_invariants(seqlens, 4, layout, p)
+
+
+def test_span_invariants_on_benchmark_shapes():
+    import workloads
+
+    for idx in (4, 5):
+        w = workloads.named(idx)
+        dt = la.BF16
+        p = _plan(list(w.seqlens), w.Hq, w.Hkv, w.D, dt, w.kv_layout, num_cus=256, ctas_per_cu=2)
+        assert p.grid == 512
+        assert p.total_iters == w.Hkv * sum(math.ceil(n / p.T_n) for n in w.seqlens)
+        _check_invariants(list(w.seqlens), w.Hkv, w.kv_layout, p)
+
+
+def test_special_cases_of_section_4_3():
+    # grid == number of output tiles: every CTA is host and finishing (FlashAttention-2 schedule)
+    seqlens = [1280, 1280]
+    p = _plan(seqlens, 3, 3, 128, la.BF16, la.KV_PADDED, num_cus=6, ctas_per_cu=1)
+    assert p.grid == 6 and p.total_iters == 60
+    for g in range(6):
+        (s,) = la.lean_attn_walk(p, seqlens, 3, la.KV_PADDED, g)
+        assert s["host"] and s["finishing"]
+    # grid an even multiple of the tile count: equal fixed splits (FlashDecoding schedule)
+    p = _plan(seqlens, 3, 3, 128, la.BF16, la.KV_PADDED, num_cus=12, ctas_per_cu=1)
+    for g in range(12):
+        (s,) = la.lean_attn_walk(p, seqlens, 3, la.KV_PADDED, g)
+        assert s["local_iter_end"] - s["local_iter"] == 5 and bool(s["host"]) == (g % 2 == 0)
+
+
+def test_argument_errors():
+    with pytest.raises(la.LeanAttnError) as e:
+        _plan([10], 3, 2, 128, la.BF16, la.KV_PADDED, num_cus=4)
+    assert e.value.status == -2
+    with pytest.raises(la.LeanAttnError) as e:
+        _plan([10], 2, 2, 96, la.BF16, la.KV_PADDED, num_cus=4)
+    assert e.value.status == -3
+    with pytest.raises(la.LeanAttnError) as e:
+        _plan([10, -1], 2, 2, 128, la.BF16, la.KV_PADDED, num_cus=4)
+    assert e.value.status == -5
+    with pytest.raises(la.LeanAttnError) as e:
+        _plan([1] * 257, 2, 2, 128, la.BF16, la.KV_PADDED, num_cus=4)
+    assert e.value.status == -6
+    with pytest.raises(la.LeanAttnError) as e:
+        _plan([10], 34, 2, 128, la.BF16, la.KV_PADDED, num_cus=4)       # group of 17
+    assert e.value.status == -2
+    with pytest.raises(la.LeanAttnError) as e:
+        _plan([10], 4, 2, 128, la.BF16, la.KV_PADDED, num_cus=4, kernel=1)  # VALU kernel needs Hq == Hkv
+    assert e.value.status == -8
+    assert la.lean_attn_workspace_size(1, 2, 2, 96, la.BF16) == 0
+    sz = la.lean_attn_workspace_size(1, 64, 8, 128, la.BF16)
+    assert sz >= 256 + 4 * 2048 + 2048 * 8 * 130 * 4 and sz % 256 == 0
+    for code in range(-9, 1):
+        assert la.lean_attn_strerror(code) not in ("", "unknown status")
