@@ -59,7 +59,7 @@ typedef enum lean_attn_kv_layout { LEAN_ATTN_KV_PADDED = 0, LEAN_ATTN_KV_PACKED 
 
 #define LEAN_ATTN_MAX_BATCH 256  /* sequences per call (the schedule table travels as kernel arguments) */
 #define LEAN_ATTN_MAX_GROUP 16   /* query heads per KV head (rows of one MFMA tile) */
-#define LEAN_ATTN_MAX_GRID 2048  /* upper bound on workgroups; sizes the workspace */
+#define LEAN_ATTN_MAX_GRID 4096  /* upper bound on workgroups; sizes the workspace */
 
 /*
  * The stream-K schedule of one call (Section 4.3 and the first lines of
@@ -71,7 +71,7 @@ typedef struct lean_attn_plan {
     int32_t T_n;              /* LeanTile size in tokens */
     int32_t T_m;              /* query rows per output tile = Hq / Hkv */
     int32_t num_output_tiles; /* B * Hkv, including tiles of empty sequences */
-    int32_t grid;             /* G: workgroups launched, <= max_resident and <= total_iters */
+    int32_t grid;             /* G: workgroups launched, <= total_iters */
     int64_t total_iters;      /* I: LeanTile iterations over all output tiles */
     int64_t iters_per_cta;    /* floor(I / G) */
     int32_t extra;            /* I mod G: the first `extra` CTAs take one more iteration */
@@ -86,12 +86,22 @@ typedef struct lean_attn_plan {
  * same attention output); only the balance does.
  */
 typedef struct lean_attn_tuning {
-    int32_t grid;          /* force G (clipped to I); must not exceed what is co-resident */
+    int32_t grid;          /* force G (clipped to I and to LEAN_ATTN_MAX_GRID) */
     int32_t ctas_per_cu;   /* workgroups per compute unit used to size the default G */
     int32_t num_cus;       /* pretend the device has this many compute units (schedule queries) */
     int32_t kernel;        /* 0 default, 1 force VALU kernel (needs Hq == Hkv), 2 force MFMA kernel */
     int32_t xcd_remap;     /* 0 default, 1 off, 2 on: place consecutive spans on one XCD */
-    int32_t spin_limit;    /* polls before a waiting host CTA gives up and reports PEER_TIMEOUT */
+    int32_t spin_limit;    /* polls before a waiting CTA gives up and reports PEER_TIMEOUT */
+    int32_t merge_fanin;   /* partials a CTA merges per level of the reduction tree; 0 default (8),
+                              >= LEAN_ATTN_MAX_GRID gives Algorithm 2's flat list: the host block
+                              merges every peer itself */
+    int32_t tile_shape;    /* 0 default; 1..5 other compiled (loads per lane, waves per workgroup)
+                              shapes, i.e. other LeanTile sizes T_n: see lean_attn_schedule */
+    int32_t grid_multiple; /* default G = units x ctas_per_cu x grid_multiple (0: library default) */
+    int32_t reserved;      /* must be 0 */
+    void* cta_clock;       /* device, 8 uint64 per CTA of the grid, or NULL: 100 MHz timestamps at
+                              kernel entry, end of streaming, end of merging, exit (last segment),
+                              then the HW_ID and XCC_ID registers and the workgroup id, one spare */
 } lean_attn_tuning;
 
 /*
@@ -131,8 +141,8 @@ int lean_attn_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, in
  * Algorithm 2), computed by the same code the kernel runs.  Writes up to
  * `max_segments` records of 8 int64 each:
  *   {tile_idx, b, h_kv, local_iter, local_iter_end, host_block, finishing_block, last_cta}
- * (last_cta is -1 unless host and not finishing) and returns the number of
- * segments, or a negative status.
+ * (last_cta: the last CTA contributing to the tile; the first one is the host
+ * block) and returns the number of segments, or a negative status.
  */
 int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, int Hkv,
                    int kv_layout, int g, int64_t* segments, int max_segments);
@@ -150,7 +160,7 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
  *   scale    multiplies q.k before the softmax (1/sqrt(D) in Eq. 1)
  *   tuning   NULL for defaults
  * Supported: D in {64, 128}, both dtypes, Hq/Hkv <= 16, B <= LEAN_ATTN_MAX_BATCH.
- * q, k_cache, v_cache must be 16-byte aligned.
+ * q, k_cache, v_cache and out must be 16-byte aligned.
  */
 int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache,
                      const int32_t* seqlens, float* out, float* lse, void* workspace,
@@ -160,12 +170,14 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache,
 
 /*
  * Measurement helper: one pass of 16-byte loads over `bytes` of device memory
- * by a persistent grid of `grid` workgroups, each reading one contiguous share
- * (the access pattern of the decode kernel without its arithmetic).  Used to
- * report the streaming-read ceiling of the machine next to the decode rate.
- * `sink` is a device pointer to at least 4 bytes.  bytes must be a multiple of 16.
+ * by `grid` workgroups of 256 threads, without any arithmetic.  mode 0: each
+ * workgroup reads one contiguous share (the access pattern of contiguous
+ * stream-K spans); mode 1: the workgroups sweep the buffer together in 32 KiB
+ * chunks dealt round-robin.  Used to report the streaming-read ceiling of the
+ * machine next to the decode rate.  `sink` is a device pointer to at least
+ * 4 bytes.  bytes must be a multiple of 16.
  */
-int lean_attn_read_probe(const void* buf, size_t bytes, void* sink, int grid, void* hip_stream);
+int lean_attn_read_probe(const void* buf, size_t bytes, void* sink, int grid, int mode, void* hip_stream);
 
 /* Static description of a status code. */
 const char* lean_attn_strerror(int status);

@@ -5,4 +5,4 @@ from .binding import (  # noqa: F401
     lean_attn_schedule, lean_attn_strerror, lean_attn_walk, lean_attn_workspace_init,
     lean_attn_workspace_size, lean_attn_workspace_status, library_path,
 )
-from .build import build  # noqa: F401
+from .buildlib import build  # noqa: F401

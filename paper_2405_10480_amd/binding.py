@@ -11,11 +11,11 @@ import ctypes
 import os
 from typing import Optional, Sequence
 
-from . import build as _build
+from . import buildlib as _build
 
 F16, BF16 = 0, 1
 KV_PADDED, KV_PACKED = 0, 1
-MAX_BATCH, MAX_GROUP, MAX_GRID = 256, 16, 2048
+MAX_BATCH, MAX_GROUP, MAX_GRID = 256, 16, 4096
 
 OK = 0
 ERR_NULL_POINTER, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE = -1, -2, -3, -4
@@ -35,6 +35,8 @@ class Tuning(ctypes.Structure):
     _fields_ = [
         ("grid", ctypes.c_int32), ("ctas_per_cu", ctypes.c_int32), ("num_cus", ctypes.c_int32),
         ("kernel", ctypes.c_int32), ("xcd_remap", ctypes.c_int32), ("spin_limit", ctypes.c_int32),
+        ("merge_fanin", ctypes.c_int32), ("tile_shape", ctypes.c_int32), ("grid_multiple", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("cta_clock", ctypes.c_void_p),
     ]
 
 
@@ -55,7 +57,7 @@ def _load():
     global _lib
     if _lib is not None:
         return _lib
-    path = _build.LIBRARY
+    path = os.environ.get("LEAN_ATTN_LIBRARY", _build.LIBRARY)  # override: measurement builds only
     if not os.path.exists(path):
         _build.build()
     lib = ctypes.CDLL(path)
@@ -74,7 +76,7 @@ def _load():
     lib.lean_attn_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i32, i32, i32, i32, i32, i64,
                                      ctypes.c_float, i32, ctypes.POINTER(Tuning), vp]
     lib.lean_attn_read_probe.restype = i32
-    lib.lean_attn_read_probe.argtypes = [vp, sz, vp, i32, vp]
+    lib.lean_attn_read_probe.argtypes = [vp, sz, vp, i32, i32, vp]
     lib.lean_attn_strerror.restype = ctypes.c_char_p
     lib.lean_attn_strerror.argtypes = [i32]
     _lib = lib
@@ -182,8 +184,8 @@ def lean_attn_decode(q, k_cache, v_cache, seqlens, out, workspace, *, Hkv: int, 
         raise LeanAttnError(rc)
 
 
-def lean_attn_read_probe(buf, sink, grid: int, stream=None) -> None:
-    rc = _load().lean_attn_read_probe(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), grid,
+def lean_attn_read_probe(buf, sink, grid: int, mode: int = 0, stream=None) -> None:
+    rc = _load().lean_attn_read_probe(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), grid, mode,
                                       _stream_handle(stream))
     if rc != OK:
         raise LeanAttnError(rc)

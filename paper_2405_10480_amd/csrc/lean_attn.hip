@@ -19,23 +19,21 @@ namespace lean {
 static_assert(kMaxBatch == LEAN_ATTN_MAX_BATCH, "header and scheduler disagree on the batch limit");
 static_assert(kMaxGrid == LEAN_ATTN_MAX_GRID, "header and workspace layout disagree on the grid limit");
 
-// Kernel variants: core x dtype x head dim.  U = 8 loads of 16 bytes per lane
-// for K and again for V per step (VALU core); 2 blocks of 16 tokens per wave per
-// step (MFMA core).  Four waves per workgroup; LeanTile = 128 tokens at D = 128
-// and 256 (VALU) / 128 (MFMA) at D = 64.
-constexpr int kNW = 4;
-constexpr int kU = 8;
-constexpr int kNBLK = 2;
+// Kernel variants: core x dtype x head dim x tile shape.
+//   VALU core:  U loads of 16 bytes per lane for K and again for V per step, NW waves;
+//               LeanTile T_n = NW * U * 64/(D/8) tokens.
+//   MFMA core:  NBLK blocks of 16 tokens per wave per step, NW waves; T_n = NW * NBLK * 16.
+// Shape 0 is the default; the others exist for the LeanTile sweep (the paper fixes the
+// tile size per architecture after an empirical sweep, Section 4.2).
 constexpr int kDefaultCtasPerCu = 2;
-
-using MhaF16D64 = MhaCore<kDtF16, 64, kU, kNW>;
-using MhaBF16D64 = MhaCore<kDtBF16, 64, kU, kNW>;
-using MhaF16D128 = MhaCore<kDtF16, 128, kU, kNW>;
-using MhaBF16D128 = MhaCore<kDtBF16, 128, kU, kNW>;
-using GqaF16D64 = GqaCore<kDtF16, 64, kNBLK, kNW>;
-using GqaBF16D64 = GqaCore<kDtBF16, 64, kNBLK, kNW>;
-using GqaF16D128 = GqaCore<kDtF16, 128, kNBLK, kNW>;
-using GqaBF16D128 = GqaCore<kDtBF16, 128, kNBLK, kNW>;
+constexpr int kDefaultFanin = 8;
+constexpr int kDefaultGridMultiple = 1;
+#ifdef LEAN_PROBE_EXPERIMENTS
+constexpr int kMaxProbeMode = 3;
+#else
+constexpr int kMaxProbeMode = 1;
+#endif
+constexpr int kNumShapes = 6;
 
 struct Variant {
     const void* fn;
@@ -48,56 +46,72 @@ static Variant variant_of() {
     return Variant{reinterpret_cast<const void*>(&lean_decode_kernel<Core>), Core::kTn, Core::kThreads};
 }
 
+template <int DT, int D>
+static Variant mha_shape(int shape) {
+    switch (shape) {
+        case 0: return variant_of<MhaCore<DT, D, 8, 4, true>>();
+        case 1: return variant_of<MhaCore<DT, D, 4, 4, true>>();
+        case 2: return variant_of<MhaCore<DT, D, 8, 4, false>>();
+        case 3: return variant_of<MhaCore<DT, D, 4, 4, false>>();
+        case 4: return variant_of<MhaCore<DT, D, 8, 8, false>>();
+        default: return variant_of<MhaCore<DT, D, 4, 8, false>>();
+    }
+}
+
+template <int DT, int D>
+static Variant gqa_shape(int shape) {
+    switch (shape) {
+        case 0: return variant_of<GqaCore<DT, D, 2, 4>>();
+        case 1: return variant_of<GqaCore<DT, D, 1, 4>>();
+        case 2: return variant_of<GqaCore<DT, D, 1, 8>>();
+        case 3: return variant_of<GqaCore<DT, D, 2, 8>>();
+        default: return variant_of<GqaCore<DT, D, 2, 4>>();  // shapes 4, 5: same as 0
+    }
+}
+
 // kernel: 0 VALU single-row core, 1 MFMA query-group core
-static bool pick_variant(int kernel, int dtype, int D, Variant* v) {
+static bool pick_variant(int kernel, int dtype, int D, int shape, Variant* v) {
+    if (shape < 0 || shape >= kNumShapes || (D != 64 && D != 128)) return false;
     const bool bf = dtype == LEAN_ATTN_BF16;
     if (kernel == 0) {
-        if (D == 64) { *v = bf ? variant_of<MhaBF16D64>() : variant_of<MhaF16D64>(); return true; }
-        if (D == 128) { *v = bf ? variant_of<MhaBF16D128>() : variant_of<MhaF16D128>(); return true; }
+        if (D == 64) *v = bf ? mha_shape<kDtBF16, 64>(shape) : mha_shape<kDtF16, 64>(shape);
+        else *v = bf ? mha_shape<kDtBF16, 128>(shape) : mha_shape<kDtF16, 128>(shape);
     } else {
-        if (D == 64) { *v = bf ? variant_of<GqaBF16D64>() : variant_of<GqaF16D64>(); return true; }
-        if (D == 128) { *v = bf ? variant_of<GqaBF16D128>() : variant_of<GqaF16D128>(); return true; }
+        if (D == 64) *v = bf ? gqa_shape<kDtBF16, 64>(shape) : gqa_shape<kDtF16, 64>(shape);
+        else *v = bf ? gqa_shape<kDtBF16, 128>(shape) : gqa_shape<kDtF16, 128>(shape);
     }
-    return false;
+    return true;
 }
 
-static int tile_tokens(int kernel, int D) {
-    if (kernel == 0) return kNW * kU * (64 / (D / 8));
-    return kNW * kNBLK * 16;
-}
-
-// Workgroups of a variant that fit on one compute unit, and the unit count, cached per device.
+// Unit count of the device and, per variant, the workgroups that fit on one unit (cached).
 struct DeviceInfo {
     int cus = 0;
-    int resident[2][2][2] = {};  // [kernel][dtype][D == 128]
-    bool ready = false;
+    int resident[2][2][2][kNumShapes] = {};  // [kernel][dtype][D == 128][shape], 0 = not yet queried
 };
 static DeviceInfo g_dev[64];
 static std::mutex g_dev_mutex;
 
-static int query_device(int kernel, int dtype, int D, int* cus, int* per_cu) {
+static int query_device(int kernel, int dtype, int D, int shape, int* cus, int* per_cu) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LEAN_ATTN_ERR_HIP;
     std::lock_guard<std::mutex> lock(g_dev_mutex);
     DeviceInfo& di = g_dev[dev];
-    if (!di.ready) {
+    if (di.cus == 0) {
         hipDeviceProp_t prop;
         if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return LEAN_ATTN_ERR_HIP;
         di.cus = prop.multiProcessorCount;
-        for (int kn = 0; kn < 2; ++kn)
-            for (int dt = 0; dt < 2; ++dt)
-                for (int dd = 0; dd < 2; ++dd) {
-                    Variant v;
-                    pick_variant(kn, dt, dd ? 128 : 64, &v);
-                    int n = 0;
-                    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, v.fn, v.threads, 0) != hipSuccess)
-                        return LEAN_ATTN_ERR_HIP;
-                    di.resident[kn][dt][dd] = n;
-                }
-        di.ready = true;
+    }
+    int& n = di.resident[kernel][dtype][D == 128][shape];
+    if (n == 0) {
+        Variant v;
+        if (!pick_variant(kernel, dtype, D, shape, &v)) return LEAN_ATTN_ERR_UNSUPPORTED;
+        int blocks = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, v.fn, v.threads, 0) != hipSuccess || blocks <= 0)
+            return LEAN_ATTN_ERR_HIP;
+        n = blocks;
     }
     *cus = di.cus;
-    *per_cu = di.resident[kernel][dtype][D == 128];
+    *per_cu = n;
     return LEAN_ATTN_OK;
 }
 
@@ -123,7 +137,8 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
     std::memset(&t, 0, sizeof t);
     if (tn) t = *tn;
     if (t.grid < 0 || t.ctas_per_cu < 0 || t.num_cus < 0 || t.kernel < 0 || t.kernel > 2 || t.xcd_remap < 0 ||
-        t.xcd_remap > 2 || t.spin_limit < 0)
+        t.xcd_remap > 2 || t.spin_limit < 0 || t.merge_fanin < 0 || t.merge_fanin == 1 || t.tile_shape < 0 ||
+        t.tile_shape >= kNumShapes || t.grid_multiple < 0 || t.reserved != 0)
         return LEAN_ATTN_ERR_TUNING;
     const int T_m = Hq / Hkv;
     int kernel = T_m == 1 ? 0 : 1;
@@ -133,7 +148,9 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
     } else if (t.kernel == 2) {
         kernel = 1;
     }
-    const int T_n = tile_tokens(kernel, D);
+    Variant var;
+    if (!pick_variant(kernel, dtype, D, t.tile_shape, &var)) return LEAN_ATTN_ERR_UNSUPPORTED;
+    const int T_n = var.T_n;
 
     int64_t iters = 0, toks = 0;
     for (int b = 0; b < B; ++b) {
@@ -157,7 +174,7 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
     int64_t resident;
     if (cus <= 0) {  // read the device: unit count and how many workgroups of this kernel fit per unit
         int hw_per_cu = 0;
-        rc = query_device(kernel, dtype, D, &cus, &hw_per_cu);
+        rc = query_device(kernel, dtype, D, t.tile_shape, &cus, &hw_per_cu);
         if (rc != LEAN_ATTN_OK) return rc;
         if (hw_per_cu <= 0) return LEAN_ATTN_ERR_HIP;
         if (per_cu <= 0) per_cu = hw_per_cu < kDefaultCtasPerCu ? hw_per_cu : kDefaultCtasPerCu;
@@ -167,10 +184,11 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
         if (per_cu <= 0) per_cu = kDefaultCtasPerCu;
         resident = (int64_t)cus * per_cu;
     }
-    if (resident > LEAN_ATTN_MAX_GRID) resident = LEAN_ATTN_MAX_GRID;
-    int64_t G = (int64_t)cus * per_cu;
+    // The grid may exceed what is resident at once: blocks only wait for lower CTA ids, which
+    // the hardware dispatched earlier, so later blocks simply start as earlier ones retire.
+    int64_t G = (int64_t)cus * per_cu * (t.grid_multiple > 0 ? t.grid_multiple : kDefaultGridMultiple);
     if (t.grid > 0) G = t.grid;
-    if (G > resident) G = resident;  // every CTA must be co-resident: hosts wait for peers
+    if (G > LEAN_ATTN_MAX_GRID) G = LEAN_ATTN_MAX_GRID;
     if (G > I) G = I;
     if (G < 1) G = 1;
 
@@ -181,7 +199,7 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
     plan->total_iters = I;
     plan->iters_per_cta = I / G;
     plan->extra = (int32_t)(I % G);
-    plan->block_threads = kNW * 64;
+    plan->block_threads = var.threads;
     plan->max_resident = (int32_t)resident;
     plan->kernel = kernel;
     if (sched) {
@@ -293,7 +311,8 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache, co
     if (!q || !k_cache || !v_cache || !seqlens || !out || !workspace) return LEAN_ATTN_ERR_NULL_POINTER;
     int rc = check_shape(B, Hq, Hkv, D, dtype, kv_layout);
     if (rc != LEAN_ATTN_OK) return rc;
-    if ((((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache) & 15) != 0) return LEAN_ATTN_ERR_BAD_SHAPE;
+    if ((((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15) != 0)
+        return LEAN_ATTN_ERR_BAD_SHAPE;
     if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < lean_attn_workspace_size(B, Hq, Hkv, D, dtype))
         return LEAN_ATTN_ERR_WORKSPACE;
 
@@ -317,7 +336,7 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache, co
     }
 
     Variant var;
-    if (!pick_variant(plan.kernel, dtype, D, &var)) return LEAN_ATTN_ERR_UNSUPPORTED;
+    if (!pick_variant(plan.kernel, dtype, D, tuning ? tuning->tile_shape : 0, &var)) return LEAN_ATTN_ERR_UNSUPPORTED;
 
     a.q = (const uint16_t*)q;
     a.k = (const uint16_t*)k_cache;
@@ -332,9 +351,12 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache, co
     a.Hq = Hq;
     a.T_m = plan.T_m;
     a.slot = slot_floats(plan.T_m, D);
-    a.xcd_remap = (tuning && tuning->xcd_remap == 2) ? 1 : 0;
+    // the remap permutes span ids against dispatch order: only safe while the whole grid is resident
+    a.xcd_remap = (tuning && tuning->xcd_remap == 2 && plan.grid <= plan.max_resident) ? 1 : 0;
     a.spin_limit = (tuning && tuning->spin_limit > 0) ? tuning->spin_limit : (1 << 22);
     a.has_empty = has_empty;
+    a.fanin = (tuning && tuning->merge_fanin >= 2) ? tuning->merge_fanin : kDefaultFanin;
+    a.cta_clock = tuning ? (unsigned long long*)tuning->cta_clock : nullptr;
     a.scale_log2e = scale * 1.4426950408889634f;
 
     void* params[] = {&a};
@@ -345,12 +367,20 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache, co
     return LEAN_ATTN_OK;
 }
 
-int lean_attn_read_probe(const void* buf, size_t bytes, void* sink, int grid, void* hip_stream) {
+int lean_attn_read_probe(const void* buf, size_t bytes, void* sink, int grid, int mode, void* hip_stream) {
     if (!buf || !sink) return LEAN_ATTN_ERR_NULL_POINTER;
-    if (bytes == 0 || (bytes & 15) != 0 || ((uintptr_t)buf & 15) != 0 || grid <= 0 || grid > 65535)
+    if (bytes == 0 || (bytes & 15) != 0 || ((uintptr_t)buf & 15) != 0 || grid <= 0 || grid > 65535 || mode < 0 ||
+        mode > kMaxProbeMode)
         return LEAN_ATTN_ERR_BAD_SHAPE;
+#ifdef LEAN_PROBE_EXPERIMENTS
+    if (mode >= 2) {
+        hipLaunchKernelGGL(lean_read_probe2_kernel, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream,
+                           (const uint4*)buf, (int64_t)(bytes / 16), (uint32_t*)sink, mode);
+        return hipGetLastError() == hipSuccess ? LEAN_ATTN_OK : LEAN_ATTN_ERR_HIP;
+    }
+#endif
     hipLaunchKernelGGL(lean_read_probe_kernel, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream, (const uint4*)buf,
-                       (int64_t)(bytes / 16), (uint32_t*)sink);
+                       (int64_t)(bytes / 16), (uint32_t*)sink, mode);
     return hipGetLastError() == hipSuccess ? LEAN_ATTN_OK : LEAN_ATTN_ERR_HIP;
 }
 

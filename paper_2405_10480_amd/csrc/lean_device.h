@@ -11,7 +11,7 @@ namespace lean {
 
 constexpr int kDtF16 = 0;
 constexpr int kDtBF16 = 1;
-constexpr int kMaxGrid = 2048;
+constexpr int kMaxGrid = 4096;
 
 // Workspace layout (bytes): [0,256) status word, [256, 256+4*kMaxGrid) flags,
 // then kMaxGrid partial slots of slot_floats floats: O~[T_m][D], m[T_m], l[T_m].
@@ -40,6 +40,8 @@ struct DecodeArgs {
     int32_t xcd_remap;
     int32_t spin_limit;
     int32_t has_empty;     // some N_b == 0: those output rows must be zeroed
+    int32_t fanin;         // children merged per level of the reduction tree (>= 2)
+    unsigned long long* cta_clock;  // optional trace, 8 words per CTA, may be null
     float scale_log2e;     // scale * log2(e): scores live in the base-2 domain
     Sched sched;
     SchedTable table;
@@ -121,24 +123,48 @@ __device__ __forceinline__ float group_allreduce_sum(float x) {
 
 __device__ __forceinline__ float xor_shuffle(float x, int lane_mask) { return __shfl_xor(x, lane_mask, 64); }
 
-// ---- Algorithm 2: Signal / Wait on flags in global memory -------------------------------
-// Signal: every thread of the workgroup has stored its share of the partial;
-// a device-scope release makes those stores visible before the flag.
-__device__ __forceinline__ void signal_arrival(uint32_t* flag) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-    __syncthreads();
-    if (threadIdx.x == 0) __hip_atomic_store(flag, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+// ---- Algorithm 2: StorePartials / Signal / Wait / LoadPartials ---------------------------
+// The workgroups of one launch run on 8 XCDs whose L2 caches are not coherent with each
+// other.  Ordinary stores followed by a device-scope release fence would write the whole
+// L2 back (and an acquire fence would invalidate it) once per publishing wave, stalling the
+// K/V streams of every workgroup on that XCD.  Instead every access to a partial or a flag
+// is itself a device-scope access (the sc1 cache-policy bit: written through to, and read
+// from, the device coherence point), so no cache-wide writeback or invalidate is needed:
+//   producer: sc1 stores of the partial; wait until they are acknowledged (s_waitcnt
+//             vmcnt(0), part of the workgroup barrier); then one sc1 store of the flag;
+//   consumer: sc1 loads of the flag until set; then sc1 loads of the partial.
+constexpr int kDeviceScope = 16;  // cache-policy operand of the buffer builtins: sc1
+
+__device__ __forceinline__ void partial_store16(buffer_rsrc r, uint32_t byte_off, f32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)byte_off, 0, kDeviceScope);
+}
+__device__ __forceinline__ void partial_store4(buffer_rsrc r, uint32_t byte_off, float v) {
+    __builtin_amdgcn_raw_buffer_store_b32(as_u32(v), r, (int)byte_off, 0, kDeviceScope);
+}
+__device__ __forceinline__ f32x4 partial_load16(buffer_rsrc r, uint32_t byte_off) {
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, kDeviceScope));
+}
+__device__ __forceinline__ float partial_load4(buffer_rsrc r, uint32_t byte_off) {
+    return as_f32(__builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, kDeviceScope));
 }
 
-// Wait: thread 0 polls the flag (bounded), then the whole workgroup acquires at
-// device scope so that its following loads observe the peer's partial.  The
-// consumer clears the flag: each flag has exactly one consumer per launch, so
-// the workspace is clean again when the kernel ends.
-__device__ __forceinline__ void wait_arrival(uint32_t* flag, uint32_t* status, int spin_limit) {
-    if (threadIdx.x == 0) {
+// Signal: the barrier waits for every thread's partial stores to be acknowledged.
+__device__ __forceinline__ void signal_arrival(uint32_t* flag) {
+    __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): stores acknowledged
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_store(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Wait for `nchild` peers at once: thread j polls the flag of CTA first + j*step (bounded).
+// The consumer clears the flags: each flag has exactly one consumer per launch, so the
+// workspace is clean again when the kernel ends.
+__device__ __forceinline__ void wait_arrivals(uint32_t* flags, int first, int step, int nchild, uint32_t* status,
+                                              int spin_limit) {
+    if ((int)threadIdx.x < nchild) {
+        uint32_t* flag = flags + first + (int)threadIdx.x * step;
         int spins = 0;
         while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-            __builtin_amdgcn_s_sleep(8);
+            __builtin_amdgcn_s_sleep(2);
             if (++spins >= spin_limit) {  // peer never arrived: report, do not hang
                 __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 break;
@@ -146,8 +172,20 @@ __device__ __forceinline__ void wait_arrival(uint32_t* flag, uint32_t* status, i
         }
         __hip_atomic_store(flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    __syncthreads();  // the partial loads that follow are issued after the flags were seen
+}
+
+// Optional per-CTA trace: 8 uint64 per CTA: timestamps (100 MHz) at kernel entry, end of
+// streaming, end of merging and exit, then the HW_ID and XCC_ID registers and the workgroup id.
+__device__ __forceinline__ void stamp(const DecodeArgs& a, int g, int slot) {
+    if (a.cta_clock && threadIdx.x == 0) {
+        a.cta_clock[8 * g + slot] = wall_clock64();
+        if (slot == 0) {
+            a.cta_clock[8 * g + 4] = __builtin_amdgcn_s_getreg((31 << 11) | 4);   // HW_REG_HW_ID
+            a.cta_clock[8 * g + 5] = __builtin_amdgcn_s_getreg((31 << 11) | 20);  // HW_REG_XCC_ID
+            a.cta_clock[8 * g + 6] = blockIdx.x;
+        }
+    }
 }
 
 }  // namespace lean

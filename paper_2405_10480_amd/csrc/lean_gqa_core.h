@@ -87,13 +87,13 @@ struct GqaCore {
     static_assert(D == 64 || D == 128, "head dim");
     using vvec = typename VVec<D>::type;
 
-    struct Smem {
+    struct alignas(16) Smem {
         float o[kStreams][kTmMax][D];
         float m[kStreams][kTmMax];
         float l[kStreams][kTmMax];
     };
 
-    __device__ static void run(const DecodeArgs& a, const Segment& sg, Smem& sm) {
+    __device__ static void run(const DecodeArgs& a, const Segment& sg, Smem& sm, int cta) {
         const int lane = threadIdx.x & 63;
         const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int r = lane & 15;   // A row / B column index of the lane
@@ -220,6 +220,7 @@ struct GqaCore {
         while (it < it_end) {
             load(kB, vB, min(it + 1, it_last));
             compute(kA, vA, it);
+            if (a.cta_clock && it == sg.local_iter && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
             load(kA, vA, min(it + 2, it_last));
             if (it + 1 < it_end) compute(kB, vB, it + 1);
             it += 2;

@@ -21,7 +21,7 @@
 
 namespace lean {
 
-template <int DT, int D, int U, int NW>
+template <int DT, int D, int U, int NW, bool DB = true>
 struct MhaCore {
     static constexpr int kD = D;
     static constexpr int kLPR = D / 8;        // lanes per row
@@ -34,7 +34,7 @@ struct MhaCore {
     static constexpr int kMinWavesPerSimd = 2;
     static_assert(D == 64 || D == 128, "head dim");
 
-    struct Smem {
+    struct alignas(16) Smem {
         float o[kStreams][kTmMax][D];
         float m[kStreams][kTmMax];
         float l[kStreams][kTmMax];
@@ -43,7 +43,7 @@ struct MhaCore {
     // Computes this workgroup's share of one output tile: LeanTile iterations
     // [sg.local_iter, sg.local_iter_end) of (sg.b, sg.h).  Leaves one un-scaled
     // partial (O~, m, l) per wave in `sm` (base-2 log domain) and ends with a barrier.
-    __device__ static void run(const DecodeArgs& a, const Segment& sg, Smem& sm) {
+    __device__ static void run(const DecodeArgs& a, const Segment& sg, Smem& sm, int cta) {
         const int lane = threadIdx.x & 63;
         const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int r = lane / kLPR;
@@ -77,6 +77,17 @@ struct MhaCore {
         };
 
         auto compute = [&](const u32x4(&kb)[U], const u32x4(&vb)[U], int step) {
+#ifdef LEAN_STRIP_COMPUTE  // measurement build only: consume the loads without the arithmetic
+            uint32_t x = 0;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                x ^= kb[u].x ^ kb[u].y ^ kb[u].z ^ kb[u].w ^ vb[u].x ^ vb[u].y ^ vb[u].z ^ vb[u].w;
+            o[0] += as_f32(x & 0x3fffffffu);
+            l_run = 1.f;
+            m_run = 0.f;
+            (void)step;
+            return;
+#endif
             const int tok0 = step * kTn + w * kCH + r;
             float s[U];
 #pragma unroll
@@ -125,19 +136,30 @@ struct MhaCore {
             }
         };
 
-        // Double-buffered walk over the LeanTile iterations.  Prefetches are
-        // unconditional (the step index is clamped) so that the loads of the
-        // next step stay in flight across the arithmetic of this one.
         const int it_end = sg.local_iter_end;
-        const int it_last = it_end - 1;
-        int it = sg.local_iter;
-        load(kA, vA, it);
-        while (it < it_end) {
-            load(kB, vB, min(it + 1, it_last));
-            compute(kA, vA, it);
-            load(kA, vA, min(it + 2, it_last));
-            if (it + 1 < it_end) compute(kB, vB, it + 1);
-            it += 2;
+        if constexpr (DB) {
+            // Double-buffered walk over the LeanTile iterations.  Prefetches are
+            // unconditional (the step index is clamped) so that the loads of the
+            // next step stay in flight across the arithmetic of this one.
+            const int it_last = it_end - 1;
+            int it = sg.local_iter;
+            load(kA, vA, it);
+            while (it < it_end) {
+                load(kB, vB, min(it + 1, it_last));
+                compute(kA, vA, it);
+                if (a.cta_clock && it == sg.local_iter && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+                load(kA, vA, min(it + 2, it_last));
+                if (it + 1 < it_end) compute(kB, vB, it + 1);
+                it += 2;
+            }
+        } else {
+            // Single-buffered: a wave issues one step's loads, consumes them, then issues the
+            // next; the other waves of the compute unit cover its memory latency.
+            for (int it = sg.local_iter; it < it_end; ++it) {
+                load(kA, vA, it);
+                compute(kA, vA, it);
+                if (a.cta_clock && it == sg.local_iter && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+            }
         }
 
         // Merge the lane rows of the wave with the re-scaling operator (butterfly).

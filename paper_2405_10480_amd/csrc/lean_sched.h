@@ -50,7 +50,8 @@ struct Segment {
     int32_t n_ctx;            // N_b
     int32_t host;             // this CTA computed the tile's first iteration
     int32_t finishing;        // this CTA's span reaches the tile's end
-    int32_t last_cta;         // last peer contributing to the tile (valid when host && !finishing)
+    int32_t first_cta;        // CTA that computed the tile's first iteration (the host block)
+    int32_t last_cta;         // last CTA contributing to the tile
     int64_t tile_iter_end;    // global iteration index one past the tile
 };
 
@@ -106,7 +107,8 @@ LEAN_HD Segment locate(const Sched& s, const SchedTable& t, int64_t it, int64_t 
     sg.local_iter_end = (int32_t)(stop - tile_iter);
     sg.host = it == tile_iter;
     sg.finishing = cta_end >= sg.tile_iter_end;
-    sg.last_cta = (sg.host && !sg.finishing) ? cta_of_iter(s, sg.tile_iter_end - 1) : -1;
+    sg.first_cta = cta_of_iter(s, tile_iter);
+    sg.last_cta = cta_of_iter(s, sg.tile_iter_end - 1);
     return sg;
 }
 

@@ -111,7 +111,7 @@ def test_bitwise_reproducible_and_workspace_reusable():
     inp = _mk(2, 16, 2, 128, "bf16", [5000, 1234], workloads.KV_PADDED, seed=9)
     first, _, ws = _run(inp)
     # poison the partial slots: a read before the peer's signal would surface as NaN
-    ws[256 + 4 * 2048:].view(torch.float32).fill_(float("nan"))
+    ws[256 + 4 * la.binding.MAX_GRID:].view(torch.float32).fill_(float("nan"))
     for _ in range(5):
         again, _, _ = _run(inp, ws=ws)
         assert np.array_equal(first, again)

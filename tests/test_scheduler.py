@@ -43,11 +43,15 @@ def test_grid_is_units_times_residency_and_spans_are_equal():
     # never more CTAs than iterations
     p = _plan([100], 2, 2, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2)
     assert p.total_iters == 2 and p.grid == 2
-    # a forced grid is honoured but clipped to what is co-resident
+    # a forced grid is honoured (it may exceed what is resident), up to the workspace limit
     p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2, grid=7)
     assert p.grid == 7 and p.extra == 16384 % 7
     p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=4, ctas_per_cu=2, grid=1000)
-    assert p.grid == 8
+    assert p.grid == 1000 and p.max_resident == 8
+    p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=4, ctas_per_cu=2, grid=100000)
+    assert p.grid == 4096
+    p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2, grid_multiple=4)
+    assert p.grid == 2048
     # query groups use the MFMA kernel, one output tile per KV head
     p = _plan([262144], 64, 8, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2)
     assert p.kernel == 1 and p.T_m == 8 and p.num_output_tiles == 8
@@ -113,10 +117,8 @@ def _check_invariants(seqlens, Hkv, layout, p):
             g, s = hosts[(b, h)]
             peers = sorted(contributors[(b, h)])
             assert peers[0] == g and peers == list(range(g, peers[-1] + 1))
-            if not s["finishing"]:
-                assert s["last_cta"] == peers[-1]
-            else:
-                assert len(peers) == 1 and s["last_cta"] == -1
+            assert s["last_cta"] == peers[-1]
+            assert bool(s["finishing"]) == (len(peers) == 1)
 
 
 @pytest.mark.parametrize("layout", [la.KV_PADDED, la.KV_PACKED])
@@ -175,6 +177,6 @@ def test_argument_errors():
     assert e.value.status == -8
     assert la.lean_attn_workspace_size(1, 2, 2, 96, la.BF16) == 0
     sz = la.lean_attn_workspace_size(1, 64, 8, 128, la.BF16)
-    assert sz >= 256 + 4 * 2048 + 2048 * 8 * 130 * 4 and sz % 256 == 0
+    assert sz >= 256 + 4 * 4096 + 4096 * 8 * 130 * 4 and sz % 256 == 0
     for code in range(-9, 1):
         assert la.lean_attn_strerror(code) not in ("", "unknown status")
