@@ -54,6 +54,8 @@ def main() -> int:
     ap.add_argument("--grid", type=int, default=0)
     ap.add_argument("--xcd-remap", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -133,6 +135,16 @@ def main() -> int:
     torch.cuda.synchronize()
     probe_gbps = one_copy * reps / (ps.elapsed_time(pe) * 1e-3) / 1e9
 
+    if args.calibrate_copy:
+        # A plain copy of known size: reads 1 GiB, writes 1 GiB.  Profiler counter runs scale their
+        # FETCH_SIZE / WRITE_SIZE readings by what the same counters report for this kernel.
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     result = {
         "metric": "decode-attention KV-cache HBM GB/s (latency in ms_per_step / latency_us)",
         "value": round(gbps_job, 1),
@@ -147,7 +159,8 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": w.dtype,
+        "dtype": w.dtype,            # element type of Q/K/V; products and sums accumulate in f32
+        "accumulate": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
                    "total_context": w.total_tokens, "kv_bytes": one_copy, "kv_layout": "packed" if w.kv_layout else "padded",

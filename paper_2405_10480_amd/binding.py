@@ -57,7 +57,7 @@ def _load():
     global _lib
     if _lib is not None:
         return _lib
-    path = os.environ.get("LEAN_ATTN_LIBRARY", _build.LIBRARY)  # override: measurement builds only
+    path = _build.LIBRARY
     if not os.path.exists(path):
         _build.build()
     lib = ctypes.CDLL(path)

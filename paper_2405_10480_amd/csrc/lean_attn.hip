@@ -28,11 +28,7 @@ static_assert(kMaxGrid == LEAN_ATTN_MAX_GRID, "header and workspace layout disag
 constexpr int kDefaultCtasPerCu = 2;
 constexpr int kDefaultFanin = 8;
 constexpr int kDefaultGridMultiple = 1;
-#ifdef LEAN_PROBE_EXPERIMENTS
-constexpr int kMaxProbeMode = 3;
-#else
 constexpr int kMaxProbeMode = 1;
-#endif
 constexpr int kNumShapes = 6;
 
 struct Variant {
@@ -372,13 +368,6 @@ int lean_attn_read_probe(const void* buf, size_t bytes, void* sink, int grid, in
     if (bytes == 0 || (bytes & 15) != 0 || ((uintptr_t)buf & 15) != 0 || grid <= 0 || grid > 65535 || mode < 0 ||
         mode > kMaxProbeMode)
         return LEAN_ATTN_ERR_BAD_SHAPE;
-#ifdef LEAN_PROBE_EXPERIMENTS
-    if (mode >= 2) {
-        hipLaunchKernelGGL(lean_read_probe2_kernel, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream,
-                           (const uint4*)buf, (int64_t)(bytes / 16), (uint32_t*)sink, mode);
-        return hipGetLastError() == hipSuccess ? LEAN_ATTN_OK : LEAN_ATTN_ERR_HIP;
-    }
-#endif
     hipLaunchKernelGGL(lean_read_probe_kernel, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream, (const uint4*)buf,
                        (int64_t)(bytes / 16), (uint32_t*)sink, mode);
     return hipGetLastError() == hipSuccess ? LEAN_ATTN_OK : LEAN_ATTN_ERR_HIP;

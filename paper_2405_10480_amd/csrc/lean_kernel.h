@@ -281,43 +281,5 @@ __global__ __launch_bounds__(256) void lean_read_probe_kernel(const uint4* buf, 
     if (acc == 0x9e3779b9u) sink[0] = acc;  // practically never true: keeps the loads alive
 }
 
-#ifdef LEAN_PROBE_EXPERIMENTS
-// two streams per workgroup (first and second half of the buffer), 8 + 8 loads in flight
-__global__ __launch_bounds__(256) void lean_read_probe2_kernel(const uint4* buf, int64_t n_vec, uint32_t* sink,
-                                                               int mode) {
-    const int G = gridDim.x;
-    const int64_t half = n_vec / 2;
-    const int64_t per = (half + G - 1) / G;
-    const int64_t lo = (int64_t)blockIdx.x * per;
-    const int64_t hi = lo + per < half ? lo + per : half;
-    uint32_t acc = 0;
-    if (mode == 2) {
-        for (int64_t i = lo + threadIdx.x; i + 7 * 256 < hi; i += 8 * 256) {
-            uint4 x[8], y[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) x[u] = buf[i + u * 256];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) y[u] = buf[half + i + u * 256];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w ^ y[u].x ^ y[u].y ^ y[u].z ^ y[u].w;
-        }
-    } else {  // mode 3: same through buffer descriptors; wave w reads the w-th 8 KiB slice of each 32 KiB
-        const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-        const buffer_rsrc ka = make_slab((const uint16_t*)buf, (uint32_t)(half * 16));
-        const buffer_rsrc va = make_slab((const uint16_t*)(buf + half), (uint32_t)(half * 16));
-        for (int64_t i = lo; i + 8 * 256 <= hi; i += 8 * 256) {
-            const uint32_t off = (uint32_t)((i + w * 512 + lane) * 16);
-            u32x4 x[8], y[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) x[u] = slab_load16(ka, off + u * 1024u);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) y[u] = slab_load16(va, off + u * 1024u);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w ^ y[u].x ^ y[u].y ^ y[u].z ^ y[u].w;
-        }
-    }
-    if (acc == 0x9e3779b9u) sink[0] = acc;
-}
-#endif
 
 }  // namespace lean

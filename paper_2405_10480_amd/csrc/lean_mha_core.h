@@ -77,17 +77,6 @@ struct MhaCore {
         };
 
         auto compute = [&](const u32x4(&kb)[U], const u32x4(&vb)[U], int step) {
-#ifdef LEAN_STRIP_COMPUTE  // measurement build only: consume the loads without the arithmetic
-            uint32_t x = 0;
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                x ^= kb[u].x ^ kb[u].y ^ kb[u].z ^ kb[u].w ^ vb[u].x ^ vb[u].y ^ vb[u].z ^ vb[u].w;
-            o[0] += as_f32(x & 0x3fffffffu);
-            l_run = 1.f;
-            m_run = 0.f;
-            (void)step;
-            return;
-#endif
             const int tok0 = step * kTn + w * kCH + r;
             float s[U];
 #pragma unroll
