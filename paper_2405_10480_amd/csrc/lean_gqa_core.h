@@ -88,7 +88,7 @@ struct GqaCore {
     using vvec = typename VVec<D>::type;
 
     struct alignas(16) Smem {
-        float o[kStreams][kTmMax][D];
+        float o[kStreams][kTmMax][D + 4];
         float m[kStreams][kTmMax];
         float l[kStreams][kTmMax];
     };
@@ -229,10 +229,14 @@ struct GqaCore {
         // l over the four k-group lanes of each head; m is already common to them.
         l_run += xor_shuffle(l_run, 16);
         l_run += xor_shuffle(l_run, 32);
+        // 16-byte stores; rows are padded by 4 floats so that the 16 heads hit different banks
 #pragma unroll
-        for (int e = 0; e < kEV; ++e) {
+        for (int i = 0; i < 4; ++i) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) sm.o[w][r][kEV * (4 * g + i) + e] = acc[e][i];
+            for (int e4 = 0; e4 < kEV; e4 += 4) {
+                const f32x4 v = {acc[e4][i], acc[e4 + 1][i], acc[e4 + 2][i], acc[e4 + 3][i]};
+                *reinterpret_cast<f32x4*>(&sm.o[w][r][kEV * (4 * g + i) + e4]) = v;
+            }
         }
         if (g == 0) {
             sm.m[w][r] = m_run;

@@ -185,6 +185,35 @@ def test_waiting_host_gives_up_instead_of_hanging():
     _check(got, got_lse, want, want_lse, "after status")
 
 
+@pytest.mark.parametrize("group", [1, 4])
+def test_every_tile_shape_and_merge_fanin(group):
+    # two output tiles shared by hundreds of CTAs: deep reduction trees, every compiled LeanTile size
+    Hkv, D = 2, 128
+    seqlens = [70001]
+    inp = _mk(1, Hkv * group, Hkv, D, "bf16", seqlens, workloads.KV_PADDED, seed=31, outlier=0.01)
+    want, want_lse = _oracle(inp)
+    for shape in range(6):
+        got, got_lse, _ = _run(inp, la.Tuning(tile_shape=shape))
+        _check(got, got_lse, want, want_lse, f"shape={shape}")
+    for fanin in (2, 3, 5, 8, 16, 4096):
+        for ctas in (1, 2):
+            got, got_lse, _ = _run(inp, la.Tuning(merge_fanin=fanin, ctas_per_cu=ctas))
+            _check(got, got_lse, want, want_lse, f"fanin={fanin} ctas={ctas}")
+
+
+@pytest.mark.parametrize("group", [1, 7])
+def test_grid_larger_than_resident(group):
+    # more workgroups than fit on the device at once: later ones start as earlier ones retire;
+    # blocks only wait for lower CTA ids, so this must neither hang nor change the result
+    Hkv, D = 4, 128
+    seqlens = [50000, 3, 120000, 9000]
+    inp = _mk(4, Hkv * group, Hkv, D, "bf16", seqlens, workloads.KV_PACKED, seed=32)
+    want, want_lse = _oracle(inp)
+    for tn in (dict(grid_multiple=4), dict(grid=4096), dict(grid=3001, merge_fanin=2), dict(grid=4096, xcd_remap=2)):
+        got, got_lse, _ = _run(inp, la.Tuning(**tn))
+        _check(got, got_lse, want, want_lse, f"{tn}")
+
+
 # ------------------------------------------------------------------ the five workloads, scaled down
 @pytest.mark.parametrize("idx,factor", [(1, 1), (2, 8), (3, 16), (4, 16), (5, 16)])
 def test_named_workloads_scaled(idx, factor):
