@@ -214,6 +214,21 @@ def test_grid_larger_than_resident(group):
         _check(got, got_lse, want, want_lse, f"{tn}")
 
 
+def test_maximum_batch_ragged():
+    # the largest batch the schedule table holds, lengths from 0 to a few tiles, both layouts
+    r = np.random.default_rng(256)
+    seqlens = [int(x) for x in r.integers(0, 700, size=la.binding.MAX_BATCH)]
+    seqlens[0], seqlens[-1], seqlens[100] = 0, 0, 1
+    for group, layout in ((1, workloads.KV_PACKED), (4, workloads.KV_PADDED)):
+        inp = _mk(len(seqlens), 2 * group, 2, 64, "f16", seqlens, layout, seed=33)
+        want, want_lse = _oracle(inp)
+        got, got_lse, _ = _run(inp)
+        _check(got, got_lse, want, want_lse, f"B=256 group={group}")
+    with pytest.raises(la.LeanAttnError) as e:
+        la.lean_attn_schedule(seqlens + [5], 2, 2, 64, la.F16, la.KV_PACKED)
+    assert e.value.status == la.binding.ERR_BATCH_TOO_LARGE
+
+
 # ------------------------------------------------------------------ the five workloads, scaled down
 @pytest.mark.parametrize("idx,factor", [(1, 1), (2, 8), (3, 16), (4, 16), (5, 16)])
 def test_named_workloads_scaled(idx, factor):

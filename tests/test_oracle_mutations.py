@@ -1,0 +1,120 @@
+"""Do the oracle's pins have teeth?  Each case plants one plausible mistake in a
+copy of the C oracle (CPU only, compiled into a temporary directory) and checks
+that the pins of test_oracle_pins.py reject the mutant: hand-computed cases,
+closed forms and the torch cross-check are re-run against the mutated library.
+"""
+import ctypes
+import json
+import math
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+import oracle
+
+SRC = os.path.join(os.path.dirname(oracle.__file__), "exact_attention.c")
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_cases.json")
+
+MUTANTS = {
+    "scale_dropped": ("scores[t] = scale * dot;", "scores[t] = dot;"),
+    "exp_sign_flipped": ("double w = exp(scores[t] - smax);", "double w = exp(smax - scores[t]);"),
+    "max_not_subtracted_in_lse": ("*lse = smax + log(z);", "*lse = log(z);"),
+    "not_normalised": ("for (int j = 0; j < D; ++j) out[j] /= z;", ""),
+    "value_row_off_by_one": ("widen_row(v_rows, kv_off + t * D, D, dtype, row);\n        for (int j = 0; j < D; ++j) out[j] += w * row[j];",
+                             "widen_row(v_rows, kv_off + (t + 1 < n ? t + 1 : t) * D, D, dtype, row);\n        for (int j = 0; j < D; ++j) out[j] += w * row[j];"),
+    "kv_head_modulo_instead_of_division": ("h = hq / group;", "h = hq % Hkv;"),
+    "last_token_skipped": ("for (int64_t t = 0; t < n; ++t) {\n        widen_row(k_rows,", "for (int64_t t = 0; t < n - (n > 1); ++t) {\n        widen_row(k_rows,"),
+    "dot_misses_last_element": ("for (int j = 0; j < D; ++j) dot += qrow[j] * row[j];", "for (int j = 0; j < D - (D > 1); ++j) dot += qrow[j] * row[j];"),
+    "bf16_shift_wrong": ("uint32_t u = ((uint32_t)bits) << 16;", "uint32_t u = ((uint32_t)bits) << 15;"),
+    "packed_offset_ignores_sequence_start": (": ((int64_t)h * total + cu[b]) * D;", ": ((int64_t)h * total) * D;"),
+    "padded_offset_ignores_head": ("? ((int64_t)(b * (int64_t)Hkv + h) * n_stride) * D", "? ((int64_t)(b * (int64_t)Hkv) * n_stride) * D"),
+}
+
+
+def _compile(tmp_path, name, old, new):
+    text = open(SRC).read()
+    assert old in text, f"mutation anchor for {name} no longer matches the oracle source"
+    path = os.path.join(tmp_path, f"{name}.c")
+    lib = os.path.join(tmp_path, f"lib{name}.so")
+    with open(path, "w") as fh:
+        fh.write(text.replace(old, new, 1))
+    subprocess.check_call(["gcc", "-O1", "-fopenmp", "-shared", "-fPIC", "-w", "-o", lib, path, "-lm"])
+    dll = ctypes.CDLL(lib)
+    dll.oracle_decode_attention.restype = ctypes.c_int
+    dll.oracle_decode_attention.argtypes = oracle._load().oracle_decode_attention.argtypes
+    return dll
+
+
+def _call(dll, q, k, v, seqlens, Hq, Hkv, D, scale, layout, n_stride, code):
+    sl = np.ascontiguousarray(np.asarray(seqlens, dtype=np.int32))
+    B = len(seqlens)
+    out = np.empty((B, Hq, D))
+    lse = np.empty((B, Hq))
+    rc = dll.oracle_decode_attention(q.ctypes.data, k.ctypes.data, v.ctypes.data, sl.ctypes.data, B, Hq, Hkv, D, code,
+                                     layout, n_stride, scale, out.ctypes.data, lse.ctypes.data, 1)
+    assert rc > 0
+    return out, lse
+
+
+def _pins_hold(dll) -> bool:
+    """A condensed run of the pins; True when every one of them passes."""
+    try:
+        # hand-computed cases (Eq. 1)
+        for case in json.load(open(GOLDEN))["cases"]:
+            q = np.array(case["q"], dtype=np.float64)
+            klog, kplain = case["k_log_of"], case["k_plain"]
+            N, D = len(klog), len(klog[0])
+            k = np.array([[math.log(klog[t][j]) if klog[t][j] is not None else kplain[t][j] for j in range(D)]
+                          for t in range(N)])
+            v = np.array(case["v"], dtype=np.float64)
+            out, lse = _call(dll, q, k, v, [N], case["Hq"], case["Hkv"], D, case["scale"], 0, N, oracle.F64)
+            if np.max(np.abs(out[0] - np.array(case["out"]))) > 1e-12:
+                return False
+            if np.max(np.abs(lse[0] - np.log(np.array(case["lse_log_of"])))) > 1e-12:
+                return False
+        # torch-free cross-check against the textbook definition on random fp64 data, GQA, two layouts
+        r = np.random.default_rng(0)
+        B, Hq, Hkv, D = 3, 4, 2, 5
+        lens = [6, 1, 9]
+        nmax = max(lens)
+        q = r.normal(size=(B, Hq, D))
+        k = r.normal(size=(B, Hkv, nmax, D))
+        v = r.normal(size=(B, Hkv, nmax, D))
+        kp = np.ascontiguousarray(np.concatenate([k[b, :, :lens[b]] for b in range(B)], axis=1))
+        vp = np.ascontiguousarray(np.concatenate([v[b, :, :lens[b]] for b in range(B)], axis=1))
+        for layout, kk, vv in ((0, k, v), (1, kp, vp)):
+            out, lse = _call(dll, q, kk, vv, lens, Hq, Hkv, D, 0.4, layout, nmax, oracle.F64)
+            for b in range(B):
+                for h in range(Hq):
+                    s = 0.4 * (k[b, h // 2, :lens[b]] @ q[b, h])
+                    wgt = np.exp(s - s.max())
+                    want = (wgt / wgt.sum()) @ v[b, h // 2, :lens[b]]
+                    if np.max(np.abs(out[b, h] - want)) > 1e-12:
+                        return False
+                    if abs(lse[b, h] - (s.max() + math.log(wgt.sum()))) > 1e-12:
+                        return False
+        # bf16 widening: q = 1.0, one token, v carries the pattern
+        bits = np.array([0x3F80, 0x4049, 0xC2F7, 0x0080, 0x3EAA], dtype=np.uint16)
+        want = (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        n = bits.size
+        out, _ = _call(dll, np.full((n, 1, 1), 0x3F80, np.uint16), np.zeros((n, 1, 1, 1), np.uint16),
+                       bits.reshape(n, 1, 1, 1).copy(), [1] * n, 1, 1, 1, 1.0, 0, 1, oracle.BF16)
+        if not np.array_equal(out.ravel(), want):
+            return False
+        return True
+    except AssertionError:
+        return False
+
+
+def test_unmutated_oracle_passes_the_condensed_pins(tmp_path):
+    dll = _compile(str(tmp_path), "identity", "double z = 0.0;", "double z = 0.0;")
+    assert _pins_hold(dll)
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_pins_reject_planted_mistake(tmp_path, name):
+    old, new = MUTANTS[name]
+    dll = _compile(str(tmp_path), name, old, new)
+    assert not _pins_hold(dll), f"the pins did not notice the planted mistake '{name}'"
