@@ -78,6 +78,9 @@ typedef struct lean_attn_plan {
     int32_t block_threads;    /* workgroup size */
     int32_t max_resident;     /* compute units x workgroups resident per unit */
     int32_t kernel;           /* 0 = VALU single-row kernel (Hq == Hkv), 1 = MFMA query-group kernel */
+    int32_t fixed_split;      /* 0: stream-K spans; s >= 1: baseline schedule, s parts per output tile,
+                                 CTA g = tile_idx*s + part, grid = num_output_tiles*s */
+    int32_t reserved;
 } lean_attn_plan;
 
 /*
@@ -98,7 +101,9 @@ typedef struct lean_attn_tuning {
     int32_t tile_shape;    /* 0 default; 1..5 other compiled (loads per lane, waves per workgroup)
                               shapes, i.e. other LeanTile sizes T_n: see lean_attn_schedule */
     int32_t grid_multiple; /* default G = units x ctas_per_cu x grid_multiple (0: library default) */
-    int32_t reserved;      /* must be 0 */
+    int32_t fixed_split;   /* 0: LeanAttention's stream-K spans.  Baseline schedules of Sections 3.3 / 4.3:
+                              s >= 1 cuts every output tile into s near-equal parts (s = 1: no split,
+                              the FlashAttention-2 schedule), -1 picks s = units*ctas_per_cu / tiles */
     void* cta_clock;       /* device, 8 uint64 per CTA of the grid, or NULL: 100 MHz timestamps at
                               kernel entry, end of streaming, end of merging, exit (last segment),
                               then the HW_ID and XCC_ID registers and the workgroup id, one spare */

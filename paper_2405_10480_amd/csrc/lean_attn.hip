@@ -134,7 +134,7 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
     if (tn) t = *tn;
     if (t.grid < 0 || t.ctas_per_cu < 0 || t.num_cus < 0 || t.kernel < 0 || t.kernel > 2 || t.xcd_remap < 0 ||
         t.xcd_remap > 2 || t.spin_limit < 0 || t.merge_fanin < 0 || t.merge_fanin == 1 || t.tile_shape < 0 ||
-        t.tile_shape >= kNumShapes || t.grid_multiple < 0 || t.reserved != 0)
+        t.tile_shape >= kNumShapes || t.grid_multiple < 0 || t.fixed_split < -1)
         return LEAN_ATTN_ERR_TUNING;
     const int T_m = Hq / Hkv;
     int kernel = T_m == 1 ? 0 : 1;
@@ -188,6 +188,20 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
     if (G > I) G = I;
     if (G < 1) G = 1;
 
+    // Baseline schedule: fixed split.  With no factor given, split so that one wave of
+    // workgroups fills the device and do not split once the output tiles alone exceed it
+    // (the behaviour the paper describes for FlashDecoding in Sections 3.3 and 6.1).
+    int split = 0;
+    if (t.fixed_split != 0) {
+        const int64_t tiles = (int64_t)B * Hkv;
+        const int64_t slots = (int64_t)cus * per_cu;
+        split = t.fixed_split > 0 ? t.fixed_split : (int)(slots / tiles);
+        if (split < 1) split = 1;
+        if (split > 128) split = 128;
+        G = tiles * split;
+        if (G > 65535 || (split > 1 && G > LEAN_ATTN_MAX_GRID)) return LEAN_ATTN_ERR_TUNING;
+    }
+
     plan->T_n = T_n;
     plan->T_m = T_m;
     plan->num_output_tiles = B * Hkv;
@@ -198,6 +212,8 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
     plan->block_threads = var.threads;
     plan->max_resident = (int32_t)resident;
     plan->kernel = kernel;
+    plan->fixed_split = split;
+    plan->reserved = 0;
     if (sched) {
         sched->B = B;
         sched->Hkv = Hkv;
@@ -207,6 +223,8 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
         sched->extra = plan->extra;
         sched->total_iters = I;
         sched->iters_per_cta = plan->iters_per_cta;
+        sched->fixed_split = split;
+        sched->pad_ = 0;
     }
     return LEAN_ATTN_OK;
 }
@@ -277,9 +295,11 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
     s.extra = plan->extra;
     s.total_iters = plan->total_iters;
     s.iters_per_cta = plan->iters_per_cta;
+    s.fixed_split = plan->fixed_split;
+    s.pad_ = 0;
     if (iters * Hkv != plan->total_iters) return LEAN_ATTN_ERR_BAD_SHAPE;
     int64_t it, end;
-    span_of(s, g, &it, &end);
+    span_of(s, t, g, &it, &end);
     int n = 0;
     while (it < end) {
         const Segment sg = locate(s, t, it, end);

@@ -164,7 +164,7 @@ __global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_d
     }
 
     int64_t cta_start, cta_end;
-    span_of(a.sched, g, &cta_start, &cta_end);
+    span_of(a.sched, a.table, g, &cta_start, &cta_end);
 
     bool parked = false;
     int parked_b = 0, parked_h = 0, parked_first = 0;

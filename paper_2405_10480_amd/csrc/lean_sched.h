@@ -11,6 +11,10 @@
 //                depend on the order, each follows its layout in memory).
 // Spans:         CTA g owns [g*q + min(g, r), +q + (g < r)) with q = I / G, r = I mod G
 //                (the paper divides I by G and is silent on a remainder).
+// Fixed split:   the schedule LeanAttention is compared against (Section 3.3) and one of
+//                its special cases (Section 4.3): every output tile is cut into `split`
+//                near-equal parts, CTA g = tile_idx*split + part, G = tiles*split; split = 1
+//                is the unsplit FlashAttention-2 schedule.  Kept as a built-in baseline.
 #pragma once
 #include <stdint.h>
 
@@ -39,6 +43,8 @@ struct Sched {
     int32_t extra;          // I mod G
     int64_t total_iters;    // I
     int64_t iters_per_cta;  // I / G
+    int32_t fixed_split;    // 0: stream-K spans; s >= 1: fixed split into s parts per output tile
+    int32_t pad_;
 };
 
 // One output-tile segment of a CTA's span (one trip of Algorithm 2's loop).
@@ -55,13 +61,7 @@ struct Segment {
     int64_t tile_iter_end;    // global iteration index one past the tile
 };
 
-LEAN_HD void span_of(const Sched& s, int g, int64_t* begin, int64_t* end) {
-    const int64_t lo = (int64_t)g * s.iters_per_cta + (g < s.extra ? g : s.extra);
-    *begin = lo;
-    *end = lo + s.iters_per_cta + (g < s.extra ? 1 : 0);
-}
-
-// The CTA whose span holds global iteration `it`.
+// The CTA whose span holds global iteration `it` (stream-K spans).
 LEAN_HD int cta_of_iter(const Sched& s, int64_t it) {
     const int64_t fat = (int64_t)s.extra * (s.iters_per_cta + 1);
     if (it < fat) return (int)(it / (s.iters_per_cta + 1));
@@ -107,9 +107,38 @@ LEAN_HD Segment locate(const Sched& s, const SchedTable& t, int64_t it, int64_t 
     sg.local_iter_end = (int32_t)(stop - tile_iter);
     sg.host = it == tile_iter;
     sg.finishing = cta_end >= sg.tile_iter_end;
-    sg.first_cta = cta_of_iter(s, tile_iter);
-    sg.last_cta = cta_of_iter(s, sg.tile_iter_end - 1);
+    if (s.fixed_split) {
+        const int parts = c_n < s.fixed_split ? c_n : s.fixed_split;
+        sg.first_cta = sg.tile_idx * s.fixed_split;
+        sg.last_cta = sg.first_cta + parts - 1;
+    } else {
+        sg.first_cta = cta_of_iter(s, tile_iter);
+        sg.last_cta = cta_of_iter(s, sg.tile_iter_end - 1);
+    }
     return sg;
+}
+
+// The range of global iterations CTA g owns (empty when begin == end).
+LEAN_HD void span_of(const Sched& s, const SchedTable& t, int g, int64_t* begin, int64_t* end) {
+    if (!s.fixed_split) {
+        const int64_t lo = (int64_t)g * s.iters_per_cta + (g < s.extra ? g : s.extra);
+        *begin = lo;
+        *end = lo + s.iters_per_cta + (g < s.extra ? 1 : 0);
+        return;
+    }
+    const int tile = g / s.fixed_split, part = g % s.fixed_split;
+    const int b = s.packed ? tile % s.B : tile / s.Hkv;
+    const int h = s.packed ? tile / s.B : tile % s.Hkv;
+    const int32_t c_n = t.cu_iters[b + 1] - t.cu_iters[b];
+    const int parts = c_n < s.fixed_split ? c_n : s.fixed_split;
+    if (part >= parts) {  // more parts than LeanTiles (or an empty sequence): nothing to do
+        *begin = *end = 0;
+        return;
+    }
+    const int64_t tile_iter = s.packed ? (int64_t)h * t.cu_iters[s.B] + t.cu_iters[b]
+                                       : (int64_t)s.Hkv * t.cu_iters[b] + (int64_t)h * c_n;
+    *begin = tile_iter + (int64_t)part * c_n / parts;
+    *end = tile_iter + (int64_t)(part + 1) * c_n / parts;
 }
 
 }  // namespace lean

@@ -214,6 +214,17 @@ def test_grid_larger_than_resident(group):
         _check(got, got_lse, want, want_lse, f"{tn}")
 
 
+@pytest.mark.parametrize("group", [1, 8])
+def test_fixed_split_baseline_schedules_give_the_same_result(group):
+    Hkv, D = 3, 128
+    seqlens = [9000, 70, 0, 33000]
+    inp = _mk(4, Hkv * group, Hkv, D, "bf16", seqlens, workloads.KV_PACKED, seed=34)
+    want, want_lse = _oracle(inp)
+    for split in (1, 2, 7, 64, -1):
+        got, got_lse, _ = _run(inp, la.Tuning(fixed_split=split))
+        _check(got, got_lse, want, want_lse, f"fixed_split={split}")
+
+
 def test_maximum_batch_ragged():
     # the largest batch the schedule table holds, lengths from 0 to a few tiles, both layouts
     r = np.random.default_rng(256)

@@ -156,6 +156,39 @@ def test_special_cases_of_section_4_3():
         assert s["local_iter_end"] - s["local_iter"] == 5 and bool(s["host"]) == (g % 2 == 0)
 
 
+@pytest.mark.parametrize("layout", [la.KV_PADDED, la.KV_PACKED])
+@pytest.mark.parametrize("split", [1, 2, 3, 16])
+def test_fixed_split_baseline_schedule(layout, split):
+    # Sections 3.3 / 4.3: every output tile cut into `split` near-equal parts (1 = no split)
+    seqlens = [1000, 5, 0, 70000, 129]
+    Hkv = 3
+    p = _plan(seqlens, Hkv, Hkv, 128, la.BF16, layout, num_cus=4, ctas_per_cu=2, fixed_split=split)
+    assert p.fixed_split == split and p.grid == len(seqlens) * Hkv * split
+    C = [math.ceil(n / p.T_n) for n in seqlens]
+    for tile in range(len(seqlens) * Hkv):
+        b, h = (tile // Hkv, tile % Hkv) if layout == la.KV_PADDED else (tile % len(seqlens), tile // len(seqlens))
+        pieces = []
+        for part in range(split):
+            segs = la.lean_attn_walk(p, seqlens, Hkv, layout, tile * split + part)
+            assert len(segs) <= 1
+            if part >= min(split, C[b]):
+                assert segs == []
+                continue
+            (s,) = segs
+            assert (s["b"], s["h"], s["tile_idx"]) == (b, h, tile)
+            assert s["last_cta"] == tile * split + min(split, C[b]) - 1
+            assert bool(s["host"]) == (part == 0) and bool(s["finishing"]) == (part == min(split, C[b]) - 1)
+            pieces.append((s["local_iter"], s["local_iter_end"]))
+        if C[b]:
+            assert pieces[0][0] == 0 and pieces[-1][1] == C[b]
+            assert all(x[1] == y[0] for x, y in zip(pieces, pieces[1:]))
+            sizes = [y - x for x, y in pieces]
+            assert max(sizes) - min(sizes) <= 1
+    # the default factor fills one wave of workgroups and stops splitting beyond it
+    assert _plan([65536], 32, 32, 128, la.BF16, layout, num_cus=256, ctas_per_cu=2, fixed_split=-1).fixed_split == 16
+    assert _plan([4096] * 32, 32, 32, 128, la.BF16, layout, num_cus=256, ctas_per_cu=2, fixed_split=-1).fixed_split == 1
+
+
 def test_argument_errors():
     with pytest.raises(la.LeanAttnError) as e:
         _plan([10], 3, 2, 128, la.BF16, la.KV_PADDED, num_cus=4)
