@@ -178,7 +178,8 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache,
  * by `grid` workgroups of 256 threads, without any arithmetic.  mode 0: each
  * workgroup reads one contiguous share (the access pattern of contiguous
  * stream-K spans); mode 1: the workgroups sweep the buffer together in 32 KiB
- * chunks dealt round-robin.  Used to report the streaming-read ceiling of the
+ * chunks dealt round-robin; modes 2, 3, 4: as mode 0 through a buffer descriptor
+ * with cache policy nt, sc1, sc0|sc1 on the loads.  Used to report the streaming-read ceiling of the
  * machine next to the decode rate.  `sink` is a device pointer to at least
  * 4 bytes.  bytes must be a multiple of 16.
  */

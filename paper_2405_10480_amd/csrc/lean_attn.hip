@@ -23,12 +23,14 @@ static_assert(kMaxGrid == LEAN_ATTN_MAX_GRID, "header and workspace layout disag
 //   VALU core:  U loads of 16 bytes per lane for K and again for V per step, NW waves;
 //               LeanTile T_n = NW * U * 64/(D/8) tokens.
 //   MFMA core:  NBLK blocks of 16 tokens per wave per step, NW waves; T_n = NW * NBLK * 16.
-// Shape 0 is the default; the others exist for the LeanTile sweep (the paper fixes the
-// tile size per architecture after an empirical sweep, Section 4.2).
-constexpr int kDefaultCtasPerCu = 2;
+// Shape 0 is the default, picked by the LeanTile sweep on MI355X (the paper fixes the tile
+// size per architecture after an empirical sweep, Section 4.2): with non-temporal loads the
+// memory system runs fastest with about 8 KiB in flight per wave and one workgroup per
+// compute unit, single-buffered: T_n = 64 tokens at D = 128 (VALU), 128 (MFMA).
+constexpr int kDefaultCtasPerCu = 1;
 constexpr int kDefaultFanin = 8;
 constexpr int kDefaultGridMultiple = 1;
-constexpr int kMaxProbeMode = 1;
+constexpr int kMaxProbeMode = 4;
 constexpr int kNumShapes = 6;
 
 struct Variant {
@@ -43,25 +45,26 @@ static Variant variant_of() {
 }
 
 template <int DT, int D>
-static Variant mha_shape(int shape) {
+static Variant mha_shape(int shape) {  // <loads per lane per stream, waves, double-buffered>
     switch (shape) {
-        case 0: return variant_of<MhaCore<DT, D, 8, 4, true>>();
-        case 1: return variant_of<MhaCore<DT, D, 4, 4, true>>();
-        case 2: return variant_of<MhaCore<DT, D, 8, 4, false>>();
-        case 3: return variant_of<MhaCore<DT, D, 4, 4, false>>();
+        case 0: return variant_of<MhaCore<DT, D, 4, 4, false>>();
+        case 1: return variant_of<MhaCore<DT, D, 8, 4, true>>();
+        case 2: return variant_of<MhaCore<DT, D, 4, 4, true>>();
+        case 3: return variant_of<MhaCore<DT, D, 8, 4, false>>();
         case 4: return variant_of<MhaCore<DT, D, 8, 8, false>>();
         default: return variant_of<MhaCore<DT, D, 4, 8, false>>();
     }
 }
 
 template <int DT, int D>
-static Variant gqa_shape(int shape) {
+static Variant gqa_shape(int shape) {  // <16-token blocks per wave per step, waves, double-buffered>
     switch (shape) {
-        case 0: return variant_of<GqaCore<DT, D, 2, 4>>();
-        case 1: return variant_of<GqaCore<DT, D, 1, 4>>();
-        case 2: return variant_of<GqaCore<DT, D, 1, 8>>();
-        case 3: return variant_of<GqaCore<DT, D, 2, 8>>();
-        default: return variant_of<GqaCore<DT, D, 2, 4>>();  // shapes 4, 5: same as 0
+        case 0: return variant_of<GqaCore<DT, D, 1, 8, false>>();
+        case 1: return variant_of<GqaCore<DT, D, 2, 4, true>>();
+        case 2: return variant_of<GqaCore<DT, D, 1, 4, true>>();
+        case 3: return variant_of<GqaCore<DT, D, 1, 8, true>>();
+        case 4: return variant_of<GqaCore<DT, D, 2, 8, false>>();
+        default: return variant_of<GqaCore<DT, D, 2, 4, false>>();
     }
 }
 

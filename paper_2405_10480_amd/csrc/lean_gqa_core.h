@@ -72,7 +72,7 @@ __device__ __forceinline__ uint32_t vdword(const typename VVec<D>::type& v, int 
     return v[i];
 }
 
-template <int DT, int D, int NBLK, int NW>
+template <int DT, int D, int NBLK, int NW, bool DB = true>
 struct GqaCore {
     static constexpr int kD = D;
     static constexpr int kTn = NW * NBLK * 16;  // LeanTile
@@ -214,16 +214,24 @@ struct GqaCore {
         };
 
         const int it_end = sg.local_iter_end;
-        const int it_last = it_end - 1;
-        int it = sg.local_iter;
-        load(kA, vA, it);
-        while (it < it_end) {
-            load(kB, vB, min(it + 1, it_last));
-            compute(kA, vA, it);
-            if (a.cta_clock && it == sg.local_iter && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
-            load(kA, vA, min(it + 2, it_last));
-            if (it + 1 < it_end) compute(kB, vB, it + 1);
-            it += 2;
+        if constexpr (DB) {
+            const int it_last = it_end - 1;
+            int it = sg.local_iter;
+            load(kA, vA, it);
+            while (it < it_end) {
+                load(kB, vB, min(it + 1, it_last));
+                compute(kA, vA, it);
+                if (a.cta_clock && it == sg.local_iter && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+                load(kA, vA, min(it + 2, it_last));
+                if (it + 1 < it_end) compute(kB, vB, it + 1);
+                it += 2;
+            }
+        } else {
+            for (int it = sg.local_iter; it < it_end; ++it) {
+                load(kA, vA, it);
+                compute(kA, vA, it);
+                if (a.cta_clock && it == sg.local_iter && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+            }
         }
 
         // l over the four k-group lanes of each head; m is already common to them.

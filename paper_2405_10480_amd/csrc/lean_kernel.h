@@ -248,13 +248,29 @@ __global__ void lean_zero_rows_kernel(float* out, float* lse, int64_t rows, int 
 // Streaming-read probe: 16-byte loads, 8 in flight per lane, folded into one word so the
 // loads cannot be dropped.  mode 0: workgroup g reads the g-th contiguous share of the
 // buffer (the access pattern of contiguous stream-K spans); mode 1: the workgroups sweep
-// the buffer together, 32 KiB chunks dealt round-robin (grid-stride).
+// the buffer together, 32 KiB chunks dealt round-robin (grid-stride); modes 2..4: as mode 0
+// through a buffer descriptor with cache policy nt, sc1, sc0|sc1 on the loads.
+template <int AUX>
+__device__ __forceinline__ uint32_t probe_slab(const uint4* buf, int64_t lo, int64_t hi) {
+    uint32_t acc = 0;
+    const int64_t span = hi - lo;  // 16-byte units, < 2^27 per workgroup
+    const buffer_rsrc r = make_slab((const uint16_t*)(buf + lo), (uint32_t)(span * 16));
+    for (int64_t i = threadIdx.x; i + 7 * 256 < span; i += 8 * 256) {
+        u32x4 x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = __builtin_amdgcn_raw_buffer_load_b128(r, (int)((i + u * 256) * 16), 0, AUX);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
+    }
+    return acc;
+}
+
 __global__ __launch_bounds__(256) void lean_read_probe_kernel(const uint4* buf, int64_t n_vec, uint32_t* sink,
                                                               int mode) {
     const int G = gridDim.x;
     uint32_t acc = 0;
     int64_t lo, hi, step;
-    if (mode == 0) {
+    if (mode != 1) {
         const int64_t per = (n_vec + G - 1) / G;
         lo = (int64_t)blockIdx.x * per;
         hi = lo + per < n_vec ? lo + per : n_vec;
@@ -264,22 +280,26 @@ __global__ __launch_bounds__(256) void lean_read_probe_kernel(const uint4* buf, 
         hi = n_vec;
         step = (int64_t)G * (8 * 256);
     }
-    int64_t i = lo + threadIdx.x;
-    for (; i + 7 * 256 < hi; i += step) {
-        uint4 x[8];
+    if (mode >= 2) {
+        if (lo < hi) acc = mode == 2 ? probe_slab<2>(buf, lo, hi) : mode == 3 ? probe_slab<16>(buf, lo, hi)
+                                                                           : probe_slab<17>(buf, lo, hi);
+    } else {
+        int64_t i = lo + threadIdx.x;
+        for (; i + 7 * 256 < hi; i += step) {
+            uint4 x[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = buf[i + u * 256];
+            for (int u = 0; u < 8; ++u) x[u] = buf[i + u * 256];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
-    }
-    if (mode == 0 || i < hi) {  // ragged end: at most one partial chunk per workgroup
-        for (; i < hi; i += 256) {
-            const uint4 x = buf[i];
-            acc ^= x.x ^ x.y ^ x.z ^ x.w;
+            for (int u = 0; u < 8; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
+        }
+        if (mode == 0 || i < hi) {  // ragged end: at most one partial chunk per workgroup
+            for (; i < hi; i += 256) {
+                const uint4 x = buf[i];
+                acc ^= x.x ^ x.y ^ x.z ^ x.w;
+            }
         }
     }
     if (acc == 0x9e3779b9u) sink[0] = acc;  // practically never true: keeps the loads alive
 }
-
 
 }  // namespace lean

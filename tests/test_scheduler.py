@@ -34,18 +34,23 @@ def test_library_exports_every_declared_symbol():
 def test_grid_is_units_times_residency_and_spans_are_equal():
     # the paper's own example: 108 units x 2 CTAs per unit = 216 (Section 4.3)
     p = _plan([65536] * 4, 32, 32, 64, la.F16, la.KV_PADDED, num_cus=108, ctas_per_cu=2)
-    assert p.T_n == 256 and p.grid == 216 and p.T_m == 1 and p.kernel == 0
-    assert p.total_iters == 4 * 32 * 256
+    assert p.T_n == 128 and p.grid == 216 and p.T_m == 1 and p.kernel == 0
+    assert p.total_iters == 4 * 32 * 512
+    # the paper's own tile sizes (256 tokens at d = 64, 128 at d = 128) are compiled shapes too
+    assert _plan([65536], 32, 32, 64, la.F16, la.KV_PADDED, num_cus=108, tile_shape=1).T_n == 256
+    assert _plan([65536], 32, 32, 128, la.F16, la.KV_PADDED, num_cus=108, tile_shape=1).T_n == 128
     assert p.iters_per_cta == p.total_iters // 216 and p.extra == p.total_iters % 216
     # MI355X: 256 units
     p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2)
-    assert (p.T_n, p.grid, p.total_iters, p.iters_per_cta, p.extra) == (128, 512, 16384, 32, 0)
+    assert (p.T_n, p.grid, p.total_iters, p.iters_per_cta, p.extra) == (64, 512, 32768, 64, 0)
+    p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=256)
+    assert p.grid == 256      # default: one workgroup per compute unit
     # never more CTAs than iterations
-    p = _plan([100], 2, 2, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2)
+    p = _plan([60], 2, 2, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2)
     assert p.total_iters == 2 and p.grid == 2
     # a forced grid is honoured (it may exceed what is resident), up to the workspace limit
     p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2, grid=7)
-    assert p.grid == 7 and p.extra == 16384 % 7
+    assert p.grid == 7 and p.extra == p.total_iters % 7
     p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=4, ctas_per_cu=2, grid=1000)
     assert p.grid == 1000 and p.max_resident == 8
     p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=4, ctas_per_cu=2, grid=100000)
@@ -142,8 +147,9 @@ def test_span_invariants_on_benchmark_shapes():
 
 
 def test_special_cases_of_section_4_3():
+    T_n = _plan([1], 3, 3, 128, la.BF16, la.KV_PADDED, num_cus=1).T_n
     # grid == number of output tiles: every CTA is host and finishing (FlashAttention-2 schedule)
-    seqlens = [1280, 1280]
+    seqlens = [10 * T_n, 10 * T_n]
     p = _plan(seqlens, 3, 3, 128, la.BF16, la.KV_PADDED, num_cus=6, ctas_per_cu=1)
     assert p.grid == 6 and p.total_iters == 60
     for g in range(6):
