@@ -30,7 +30,7 @@ static_assert(kMaxGrid == LEAN_ATTN_MAX_GRID, "header and workspace layout disag
 constexpr int kDefaultCtasPerCu = 1;
 constexpr int kDefaultFanin = 8;
 constexpr int kDefaultGridMultiple = 1;
-constexpr int kMaxProbeMode = 4;
+constexpr int kMaxProbeMode = 5;
 constexpr int kNumShapes = 6;
 
 struct Variant {

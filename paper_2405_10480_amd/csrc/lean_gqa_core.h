@@ -21,8 +21,15 @@
 //
 // P is split into a high and a low 16-bit part (P = P_hi + P_lo, two MFMAs per
 // operand) so that rounding P to the input precision never limits accuracy.
-// K and V go from global memory straight to the MFMA operand registers; LDS is
-// used only to hand the per-wave partials to the workgroup epilogue.
+//
+// K is loaded with the same fully coalesced pattern as V (whole rows per group of 16
+// lanes).  The A operand of S^T needs a different lane<->row assignment (lane r holds
+// a token, lane group g a 16-byte piece of each quarter row); loading that pattern
+// straight from memory reads 16-byte pieces strided over 16 rows and streams at only
+// 6.0 instead of 7.1 TB/s on this machine, so the K tile of a wave takes a detour
+// through a wave-private LDS area (padded rows, conflict-free both ways, no barrier:
+// the LDS queue of a wave is in order).  V goes from global memory straight to the
+// MFMA operand registers.
 #pragma once
 #include "lean_device.h"
 
@@ -87,10 +94,19 @@ struct GqaCore {
     static_assert(D == 64 || D == 128, "head dim");
     using vvec = typename VVec<D>::type;
 
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kStageRow = kRowBytes + 16;                 // padded K row in LDS
+    static constexpr int kStageVec = NBLK * 16 * kStageRow / 16;     // uint4 per wave
+    // Per wave: its K staging area while streaming, its partial (O~) at segment end.
+    union alignas(16) WaveArea {
+        float o[kTmMax][D + 4];
+        u32x4 k[kStageVec];
+    };
     struct alignas(16) Smem {
-        float o[kStreams][kTmMax][D + 4];
+        WaveArea area[kStreams];
         float m[kStreams][kTmMax];
         float l[kStreams][kTmMax];
+        __device__ const float* o_at(int stream, int row, int col) const { return &area[stream].o[row][col]; }
     };
 
     __device__ static void run(const DecodeArgs& a, const Segment& sg, Smem& sm, int cta) {
@@ -104,13 +120,15 @@ struct GqaCore {
         const int64_t row0 = a.sched.packed
                                  ? (int64_t)sg.h * a.total_rows + a.table.cu_tok[sg.b]
                                  : ((int64_t)sg.b * a.sched.Hkv + sg.h) * a.kv_seq_stride;
-        constexpr uint32_t kRowBytes = D * 2;
         const uint32_t slab_bytes = (uint32_t)n_ctx * kRowBytes;
         const buffer_rsrc k_slab = make_slab(a.k + row0 * D, slab_bytes);
         const buffer_rsrc v_slab = make_slab(a.v + row0 * D, slab_bytes);
         const int k_tok = 4 * (r & 3) + (r >> 2);  // token (within a block) this lane feeds as A row r
-        const uint32_t k_lane_off = (uint32_t)(w * kCH + k_tok) * kRowBytes + (uint32_t)g * 16u;
+        // K and V: lane (r, g) loads kEV elements at column r of row 4*j + g, j = 0..3
         const uint32_t v_lane_off = (uint32_t)(w * kCH + g) * kRowBytes + (uint32_t)r * (kEV * 2u);
+        char* stage = reinterpret_cast<char*>(sm.area[w].k);
+        const uint32_t stage_wr = (uint32_t)g * kStageRow + (uint32_t)r * (kEV * 2u);   // + (blk*16 + 4*j) rows
+        const uint32_t stage_rd = (uint32_t)k_tok * kStageRow + (uint32_t)g * 16u;      // + blk*16 rows + 64*c2
 
         // Q^T as B operands: lane (h = r, g) holds Q[h][32*c2 + 8*g .. +8), zero rows past T_m.
         u32x4 qb[kKC];
@@ -129,43 +147,62 @@ struct GqaCore {
 #pragma unroll
         for (int e = 0; e < kEV; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        u32x4 kA[NBLK][kKC], kB[NBLK][kKC];
+        vvec kA[NBLK][4], kB[NBLK][4];
         vvec vA[NBLK][4], vB[NBLK][4];
 
-        // K: 16-byte pieces, row-strided (lane r -> its token, lane group g -> 16 B of each
-        // 64-byte quarter-row).  V: per j one fully coalesced wave-wide load of 4 rows.
-        auto load = [&](u32x4(&kb)[NBLK][kKC], vvec(&vb)[NBLK][4], int step) {
-            const uint32_t koff = k_lane_off + (uint32_t)step * (kTn * kRowBytes);
-            const uint32_t voff = v_lane_off + (uint32_t)step * (kTn * kRowBytes);
+        // Per j one fully coalesced wave-wide load of 4 rows, for K and for V.
+        auto load = [&](vvec(&kb)[NBLK][4], vvec(&vb)[NBLK][4], int step) {
+            const uint32_t off = v_lane_off + (uint32_t)step * (kTn * kRowBytes);
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk) {
 #pragma unroll
-                for (int c2 = 0; c2 < kKC; ++c2)
-                    kb[blk][c2] = slab_load16(k_slab, koff + (uint32_t)(blk * 16) * kRowBytes + c2 * 64u);
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t o = off + (uint32_t)(blk * 16 + 4 * j) * kRowBytes;
+                    if constexpr (D == 128) kb[blk][j] = slab_load16(k_slab, o);
+                    else kb[blk][j] = slab_load8(k_slab, o);
+                }
             }
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const uint32_t o = voff + (uint32_t)(blk * 16 + 4 * j) * kRowBytes;
+                    const uint32_t o = off + (uint32_t)(blk * 16 + 4 * j) * kRowBytes;
                     if constexpr (D == 128) vb[blk][j] = slab_load16(v_slab, o);
                     else vb[blk][j] = slab_load8(v_slab, o);
                 }
             }
         };
 
-        auto compute = [&](const u32x4(&kb)[NBLK][kKC], const vvec(&vb)[NBLK][4], int step) {
+        auto compute = [&](const vvec(&kraw)[NBLK][4], const vvec(&vb)[NBLK][4], int step) {
             const int base = step * kTn + w * kCH;
+            // K rows -> wave-private LDS -> A-operand registers (lane r: token k_tok, lane group g: piece)
+            u32x4 kb[NBLK][kKC];
+#pragma unroll
+            for (int blk = 0; blk < NBLK; ++blk) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    *reinterpret_cast<vvec*>(stage + stage_wr + (uint32_t)(blk * 16 + 4 * j) * kStageRow) = kraw[blk][j];
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int blk = 0; blk < NBLK; ++blk) {
+#pragma unroll
+                for (int c2 = 0; c2 < kKC; ++c2)
+                    kb[blk][c2] = *reinterpret_cast<const u32x4*>(stage + stage_rd + (uint32_t)(blk * 16) * kStageRow + c2 * 64u);
+            }
+            __builtin_amdgcn_wave_barrier();
             f32x4 s[NBLK];
             float mx = -INFINITY;
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk) {
-                f32x4 c = {0.f, 0.f, 0.f, 0.f};
+                // two accumulators halve the dependent MFMA chain over the head dim
+                f32x4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int c2 = 0; c2 < kKC; ++c2) {
-                    c = mfma16<DT>(make_uint2(kb[blk][c2].x, kb[blk][c2].y), make_uint2(qb[c2].x, qb[c2].y), c);
-                    c = mfma16<DT>(make_uint2(kb[blk][c2].z, kb[blk][c2].w), make_uint2(qb[c2].z, qb[c2].w), c);
+                    c0 = mfma16<DT>(make_uint2(kb[blk][c2].x, kb[blk][c2].y), make_uint2(qb[c2].x, qb[c2].y), c0);
+                    c1 = mfma16<DT>(make_uint2(kb[blk][c2].z, kb[blk][c2].w), make_uint2(qb[c2].z, qb[c2].w), c1);
                 }
+                f32x4 c = c0 + c1;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     float x = c[i] * a.scale_log2e;
@@ -175,12 +212,21 @@ struct GqaCore {
                 }
                 s[blk] = c;
             }
-            mx = fmaxf(mx, xor_shuffle(mx, 16));
-            mx = fmaxf(mx, xor_shuffle(mx, 32));
-            const float m_new = fmaxf(m_run, mx);
-            const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = fast_exp2(m_run - m_ref);
-            m_run = m_new;
+            // The reference maximum m_run of a head is shared by its four k-group lanes.  It is
+            // only raised when some score of the wave exceeds it by more than kSlack (base-2
+            // units): any reference gives the same O~/l, so between updates P may reach 2^kSlack
+            // and the cross-lane maximum and the re-scaling of O stay off the common path.
+            constexpr float kSlack = 8.f;
+            float alpha = 1.f;
+            if (__any(mx > m_run + kSlack)) {
+                mx = fmaxf(mx, xor_shuffle(mx, 16));
+                mx = fmaxf(mx, xor_shuffle(mx, 32));
+                const float m_new = fmaxf(m_run, mx);
+                const float m_new_ref = m_new == -INFINITY ? 0.f : m_new;
+                alpha = fast_exp2(m_run - m_new_ref);
+                m_run = m_new;
+            }
+            const float m_ref = m_run == -INFINITY ? 0.f : m_run;
             float psum = 0.f;
             uint2 p_hi[NBLK], p_lo[NBLK];
 #pragma unroll
@@ -213,24 +259,33 @@ struct GqaCore {
             }
         };
 
-        const int it_end = sg.local_iter_end;
+        // The LeanTile iterations of the segment are visited in ascending order by every CTA.
+        // (A CTA-specific rotated order was tried: it breaks the lockstep in which equally
+        // aligned spans sweep memory, and on this machine that lockstep is faster.)
+        const int it_first = sg.local_iter;
+        const int n_it = sg.local_iter_end - sg.local_iter;
+        auto iter_at = [&](int k) { return it_first + (k < n_it ? k : n_it - 1); };  // clamped: prefetches re-read
         if constexpr (DB) {
-            const int it_last = it_end - 1;
-            int it = sg.local_iter;
-            load(kA, vA, it);
-            while (it < it_end) {
-                load(kB, vB, min(it + 1, it_last));
-                compute(kA, vA, it);
-                if (a.cta_clock && it == sg.local_iter && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
-                load(kA, vA, min(it + 2, it_last));
-                if (it + 1 < it_end) compute(kB, vB, it + 1);
-                it += 2;
+            // Double-buffered walk: prefetches are unconditional so that the loads of the next
+            // step stay in flight across the arithmetic of this one.
+            int k = 0;
+            load(kA, vA, iter_at(0));
+            while (k < n_it) {
+                load(kB, vB, iter_at(k + 1));
+                compute(kA, vA, iter_at(k));
+                if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+                load(kA, vA, iter_at(k + 2));
+                if (k + 1 < n_it) compute(kB, vB, iter_at(k + 1));
+                k += 2;
             }
         } else {
-            for (int it = sg.local_iter; it < it_end; ++it) {
+            // Single-buffered: a wave issues one step's loads, consumes them, then issues the
+            // next; the other waves of the compute unit cover its memory latency.
+            for (int k = 0; k < n_it; ++k) {
+                const int it = iter_at(k);
                 load(kA, vA, it);
                 compute(kA, vA, it);
-                if (a.cta_clock && it == sg.local_iter && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+                if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
             }
         }
 
@@ -243,7 +298,7 @@ struct GqaCore {
 #pragma unroll
             for (int e4 = 0; e4 < kEV; e4 += 4) {
                 const f32x4 v = {acc[e4][i], acc[e4 + 1][i], acc[e4 + 2][i], acc[e4 + 3][i]};
-                *reinterpret_cast<f32x4*>(&sm.o[w][r][kEV * (4 * g + i) + e4]) = v;
+                *reinterpret_cast<f32x4*>(&sm.area[w].o[r][kEV * (4 * g + i) + e4]) = v;
             }
         }
         if (g == 0) {

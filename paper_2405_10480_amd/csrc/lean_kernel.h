@@ -193,7 +193,7 @@ __global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_d
                 for (int p = 0; p < Core::kStreams; ++p) {
                     const float wgt = fast_exp2(sm.m[p][row] - m_ref);
                     own.l[i] += wgt * sm.l[p][row];
-                    own.o[i] += wgt * *reinterpret_cast<const f32x4*>(&sm.o[p][row][col]);
+                    own.o[i] += wgt * *reinterpret_cast<const f32x4*>(sm.o_at(p, row, col));
                 }
                 own.m[i] = m;
             }
@@ -265,6 +265,27 @@ __device__ __forceinline__ uint32_t probe_slab(const uint4* buf, int64_t lo, int
     return acc;
 }
 
+// mode 5: the K access pattern of the MFMA core: per wave-wide load, lane (r = lane%16,
+// g = lane/16) reads 16 bytes of row r at byte 64*c + 16*g of a 256-byte row (non-temporal).
+__device__ __forceinline__ uint32_t probe_rowstrided(const uint4* buf, int64_t lo, int64_t hi) {
+    uint32_t acc = 0;
+    const int64_t span = hi - lo;
+    const buffer_rsrc r = make_slab((const uint16_t*)(buf + lo), (uint32_t)(span * 16));
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const uint32_t lane_off = (uint32_t)(lane & 15) * 256u + (uint32_t)(lane >> 4) * 16u;
+    // a workgroup step = 4 waves x 2 blocks of 16 rows x 256 B = 32 KiB
+    for (int64_t i = 0; (i + 1) * 2048 <= span; ++i) {
+        const uint32_t base = (uint32_t)(i * 32768) + (uint32_t)w * 8192u + lane_off;
+        u32x4 x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            x[u] = __builtin_amdgcn_raw_buffer_load_b128(r, (int)(base + (u >> 2) * 4096u + (u & 3) * 64u), 0, 2);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
+    }
+    return acc;
+}
+
 __global__ __launch_bounds__(256) void lean_read_probe_kernel(const uint4* buf, int64_t n_vec, uint32_t* sink,
                                                               int mode) {
     const int G = gridDim.x;
@@ -281,8 +302,9 @@ __global__ __launch_bounds__(256) void lean_read_probe_kernel(const uint4* buf, 
         step = (int64_t)G * (8 * 256);
     }
     if (mode >= 2) {
-        if (lo < hi) acc = mode == 2 ? probe_slab<2>(buf, lo, hi) : mode == 3 ? probe_slab<16>(buf, lo, hi)
-                                                                           : probe_slab<17>(buf, lo, hi);
+        if (lo < hi)
+            acc = mode == 2 ? probe_slab<2>(buf, lo, hi) : mode == 3 ? probe_slab<16>(buf, lo, hi)
+                  : mode == 4 ? probe_slab<17>(buf, lo, hi) : probe_rowstrided(buf, lo, hi);
     } else {
         int64_t i = lo + threadIdx.x;
         for (; i + 7 * 256 < hi; i += step) {

@@ -38,6 +38,7 @@ struct MhaCore {
         float o[kStreams][kTmMax][D];
         float m[kStreams][kTmMax];
         float l[kStreams][kTmMax];
+        __device__ const float* o_at(int stream, int row, int col) const { return &o[stream][row][col]; }
     };
 
     // Computes this workgroup's share of one output tile: LeanTile iterations
@@ -125,29 +126,33 @@ struct MhaCore {
             }
         };
 
-        const int it_end = sg.local_iter_end;
+        // The LeanTile iterations of the segment are visited in ascending order by every CTA.
+        // (A CTA-specific rotated order was tried: it breaks the lockstep in which equally
+        // aligned spans sweep memory, and on this machine that lockstep is faster.)
+        const int it_first = sg.local_iter;
+        const int n_it = sg.local_iter_end - sg.local_iter;
+        auto iter_at = [&](int k) { return it_first + (k < n_it ? k : n_it - 1); };  // clamped: prefetches re-read
         if constexpr (DB) {
-            // Double-buffered walk over the LeanTile iterations.  Prefetches are
-            // unconditional (the step index is clamped) so that the loads of the
-            // next step stay in flight across the arithmetic of this one.
-            const int it_last = it_end - 1;
-            int it = sg.local_iter;
-            load(kA, vA, it);
-            while (it < it_end) {
-                load(kB, vB, min(it + 1, it_last));
-                compute(kA, vA, it);
-                if (a.cta_clock && it == sg.local_iter && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
-                load(kA, vA, min(it + 2, it_last));
-                if (it + 1 < it_end) compute(kB, vB, it + 1);
-                it += 2;
+            // Double-buffered walk: prefetches are unconditional so that the loads of the next
+            // step stay in flight across the arithmetic of this one.
+            int k = 0;
+            load(kA, vA, iter_at(0));
+            while (k < n_it) {
+                load(kB, vB, iter_at(k + 1));
+                compute(kA, vA, iter_at(k));
+                if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+                load(kA, vA, iter_at(k + 2));
+                if (k + 1 < n_it) compute(kB, vB, iter_at(k + 1));
+                k += 2;
             }
         } else {
             // Single-buffered: a wave issues one step's loads, consumes them, then issues the
             // next; the other waves of the compute unit cover its memory latency.
-            for (int it = sg.local_iter; it < it_end; ++it) {
+            for (int k = 0; k < n_it; ++k) {
+                const int it = iter_at(k);
                 load(kA, vA, it);
                 compute(kA, vA, it);
-                if (a.cta_clock && it == sg.local_iter && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+                if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
             }
         }
 
