@@ -63,7 +63,7 @@ static Variant gqa_shape(int shape) {  // <16-token blocks per wave per step, wa
         case 1: return variant_of<GqaCore<DT, D, 2, 4, true>>();
         case 2: return variant_of<GqaCore<DT, D, 1, 4, true>>();
         case 3: return variant_of<GqaCore<DT, D, 1, 8, true>>();
-        case 4: return variant_of<GqaCore<DT, D, 2, 8, false>>();
+        case 4: return variant_of<GqaCore<DT, D, 1, 4, false>>();
         default: return variant_of<GqaCore<DT, D, 2, 4, false>>();
     }
 }
