@@ -26,7 +26,7 @@ static_assert(kMaxGrid == LEAN_ATTN_MAX_GRID, "header and workspace layout disag
 // Shape 0 is the default, picked by the LeanTile sweep on MI355X (the paper fixes the tile
 // size per architecture after an empirical sweep, Section 4.2): with non-temporal loads the
 // memory system runs fastest with about 8 KiB in flight per wave and one workgroup per
-// compute unit, single-buffered: T_n = 64 tokens at D = 128 (VALU), 128 (MFMA).
+// compute unit of four waves, single-buffered: T_n = 64 tokens at D = 128 for both cores.
 constexpr int kDefaultCtasPerCu = 1;
 constexpr int kDefaultFanin = 8;
 constexpr int kDefaultGridMultiple = 1;
@@ -59,11 +59,11 @@ static Variant mha_shape(int shape) {  // <loads per lane per stream, waves, dou
 template <int DT, int D>
 static Variant gqa_shape(int shape) {  // <16-token blocks per wave per step, waves, double-buffered>
     switch (shape) {
-        case 0: return variant_of<GqaCore<DT, D, 1, 8, false>>();
+        case 0: return variant_of<GqaCore<DT, D, 1, 4, false>>();
         case 1: return variant_of<GqaCore<DT, D, 2, 4, true>>();
         case 2: return variant_of<GqaCore<DT, D, 1, 4, true>>();
         case 3: return variant_of<GqaCore<DT, D, 1, 8, true>>();
-        case 4: return variant_of<GqaCore<DT, D, 1, 4, false>>();
+        case 4: return variant_of<GqaCore<DT, D, 1, 8, false>>();
         default: return variant_of<GqaCore<DT, D, 2, 4, false>>();
     }
 }
