@@ -166,6 +166,8 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
  *   tuning   NULL for defaults
  * Supported: D in {64, 128}, both dtypes, Hq/Hkv <= 16, B <= LEAN_ATTN_MAX_BATCH.
  * q, k_cache, v_cache and out must be 16-byte aligned.
+ * The first call per device and kernel variant reads the device's unit count and the
+ * kernel's residency from the runtime (cached afterwards): make it outside graph capture.
  */
 int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache,
                      const int32_t* seqlens, float* out, float* lse, void* workspace,

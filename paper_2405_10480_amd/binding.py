@@ -83,8 +83,18 @@ def _load():
     return lib
 
 
+_seqlens_cache: dict = {}
+
+
 def _seqlens_array(seqlens: Sequence[int]):
-    arr = (ctypes.c_int32 * len(seqlens))(*[int(x) for x in seqlens])
+    """Host int32 array for the C side; repeated calls with the same lengths reuse one array."""
+    key = tuple(seqlens)
+    arr = _seqlens_cache.get(key)
+    if arr is None:
+        if len(_seqlens_cache) > 64:
+            _seqlens_cache.clear()
+        arr = (ctypes.c_int32 * len(key))(*[int(x) for x in key])
+        _seqlens_cache[key] = arr
     return arr
 
 

@@ -225,6 +225,38 @@ def test_fixed_split_baseline_schedules_give_the_same_result(group):
         _check(got, got_lse, want, want_lse, f"fixed_split={split}")
 
 
+def test_graph_replay_matches_eager():
+    # The decode call allocates nothing, takes its schedule by value and leaves the workspace
+    # flags clean, so it can be captured once and replayed.  Replays are interleaved with eager
+    # work and synchronisations; every replay must reproduce the eager result bit for bit.
+    inp = _mk(2, 16, 2, 128, "bf16", [30000, 4097], workloads.KV_PACKED, seed=35)
+    w = inp.w
+    want, want_lse = _oracle(inp)
+    eager, _, ws = _run(inp)
+    out = torch.zeros(w.B, w.Hq, w.D, dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        la.lean_attn_decode(inp.q, inp.k, inp.v, inp.seqlens, out, ws, Hkv=w.Hkv, kv_layout=w.kv_layout,
+                            kv_seq_stride=w.n_stride, scale=w.scale)     # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        la.lean_attn_decode(inp.q, inp.k, inp.v, inp.seqlens, out, ws, Hkv=w.Hkv, kv_layout=w.kv_layout,
+                            kv_seq_stride=w.n_stride, scale=w.scale)
+    for i in range(4):
+        out.fill_(float("nan"))
+        scratch = torch.randn(1 << 20, device="cuda").sum()          # unrelated eager work in between
+        graph.replay()
+        torch.cuda.synchronize()
+        assert la.lean_attn_workspace_status(ws) == 0
+        got = out.cpu().numpy()
+        assert np.array_equal(got, eager), f"replay {i} differs from the eager launch"
+        del scratch
+    _check(got, None, want, want_lse, "graph replay")
+
+
 def test_maximum_batch_ragged():
     # the largest batch the schedule table holds, lengths from 0 to a few tiles, both layouts
     r = np.random.default_rng(256)
