@@ -164,7 +164,7 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
  *   kv_seq_stride  rows between consecutive (b, h) slabs in the PADDED layout
  *   scale    multiplies q.k before the softmax (1/sqrt(D) in Eq. 1)
  *   tuning   NULL for defaults
- * Supported: D in {64, 128}, both dtypes, Hq/Hkv <= 16, B <= LEAN_ATTN_MAX_BATCH.
+ * Supported: D in {64, 128, 256}, both dtypes, Hq/Hkv <= 16, B <= LEAN_ATTN_MAX_BATCH.
  * q, k_cache, v_cache and out must be 16-byte aligned.
  * The first call per device and kernel variant reads the device's unit count and the
  * kernel's residency from the runtime (cached afterwards): make it outside graph capture.

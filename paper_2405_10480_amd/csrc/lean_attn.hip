@@ -68,16 +68,20 @@ static Variant gqa_shape(int shape) {  // <16-token blocks per wave per step, wa
     }
 }
 
+static int dim_index(int D) { return D == 64 ? 0 : D == 128 ? 1 : D == 256 ? 2 : -1; }
+
 // kernel: 0 VALU single-row core, 1 MFMA query-group core
 static bool pick_variant(int kernel, int dtype, int D, int shape, Variant* v) {
-    if (shape < 0 || shape >= kNumShapes || (D != 64 && D != 128)) return false;
+    if (shape < 0 || shape >= kNumShapes || dim_index(D) < 0) return false;
     const bool bf = dtype == LEAN_ATTN_BF16;
     if (kernel == 0) {
         if (D == 64) *v = bf ? mha_shape<kDtBF16, 64>(shape) : mha_shape<kDtF16, 64>(shape);
-        else *v = bf ? mha_shape<kDtBF16, 128>(shape) : mha_shape<kDtF16, 128>(shape);
+        else if (D == 128) *v = bf ? mha_shape<kDtBF16, 128>(shape) : mha_shape<kDtF16, 128>(shape);
+        else *v = bf ? mha_shape<kDtBF16, 256>(shape) : mha_shape<kDtF16, 256>(shape);
     } else {
         if (D == 64) *v = bf ? gqa_shape<kDtBF16, 64>(shape) : gqa_shape<kDtF16, 64>(shape);
-        else *v = bf ? gqa_shape<kDtBF16, 128>(shape) : gqa_shape<kDtF16, 128>(shape);
+        else if (D == 128) *v = bf ? gqa_shape<kDtBF16, 128>(shape) : gqa_shape<kDtF16, 128>(shape);
+        else *v = bf ? gqa_shape<kDtBF16, 256>(shape) : gqa_shape<kDtF16, 256>(shape);
     }
     return true;
 }
@@ -85,7 +89,7 @@ static bool pick_variant(int kernel, int dtype, int D, int shape, Variant* v) {
 // Unit count of the device and, per variant, the workgroups that fit on one unit (cached).
 struct DeviceInfo {
     int cus = 0;
-    int resident[2][2][2][kNumShapes] = {};  // [kernel][dtype][D == 128][shape], 0 = not yet queried
+    int resident[2][2][3][kNumShapes] = {};  // [kernel][dtype][head dim][shape], 0 = not yet queried
 };
 static DeviceInfo g_dev[64];
 static std::mutex g_dev_mutex;
@@ -100,7 +104,8 @@ static int query_device(int kernel, int dtype, int D, int shape, int* cus, int* 
         if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return LEAN_ATTN_ERR_HIP;
         di.cus = prop.multiProcessorCount;
     }
-    int& n = di.resident[kernel][dtype][D == 128][shape];
+    if (dim_index(D) < 0) return LEAN_ATTN_ERR_UNSUPPORTED;
+    int& n = di.resident[kernel][dtype][dim_index(D)][shape];
     if (n == 0) {
         Variant v;
         if (!pick_variant(kernel, dtype, D, shape, &v)) return LEAN_ATTN_ERR_UNSUPPORTED;
@@ -118,7 +123,7 @@ static int check_shape(int B, int Hq, int Hkv, int D, int dtype, int kv_layout) 
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return LEAN_ATTN_ERR_BAD_SHAPE;
     if (Hq / Hkv > LEAN_ATTN_MAX_GROUP) return LEAN_ATTN_ERR_BAD_SHAPE;
     if (B > LEAN_ATTN_MAX_BATCH) return LEAN_ATTN_ERR_BATCH_TOO_LARGE;
-    if (D != 64 && D != 128) return LEAN_ATTN_ERR_UNSUPPORTED;
+    if (dim_index(D) < 0) return LEAN_ATTN_ERR_UNSUPPORTED;
     if (dtype != LEAN_ATTN_F16 && dtype != LEAN_ATTN_BF16) return LEAN_ATTN_ERR_UNSUPPORTED;
     if (kv_layout != LEAN_ATTN_KV_PADDED && kv_layout != LEAN_ATTN_KV_PACKED) return LEAN_ATTN_ERR_UNSUPPORTED;
     return LEAN_ATTN_OK;

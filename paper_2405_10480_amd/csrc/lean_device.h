@@ -117,11 +117,13 @@ __device__ __forceinline__ float dpp_move(float x) {
 // quad_perm[1,0,3,2], quad_perm[2,3,0,1], row_half_mirror, row_mirror.
 template <int LANES>
 __device__ __forceinline__ float group_allreduce_sum(float x) {
-    static_assert(LANES == 8 || LANES == 16, "row of 8 or 16 lanes");
+    static_assert(LANES == 8 || LANES == 16 || LANES == 32, "row of 8, 16 or 32 lanes");
     x += dpp_move<0xB1>(x);
     x += dpp_move<0x4E>(x);
     x += dpp_move<0x141>(x);
-    if constexpr (LANES == 16) x += dpp_move<0x140>(x);
+    if constexpr (LANES >= 16) x += dpp_move<0x140>(x);
+    // lanes l and l^16: ds_swizzle in bit mode (and 0x1f, or 0, xor 0x10)
+    if constexpr (LANES == 32) x += as_f32((uint32_t)__builtin_amdgcn_ds_swizzle((int)as_u32(x), 0x401F));
     return x;
 }
 

@@ -17,7 +17,8 @@
 //     coalesced (one contiguous KiB each at D = 128), and the 4-token x D/16
 //     sub-block a lane holds is transposed in registers (v_perm_b32) into the
 //     D/16 A operands.  Accumulator e, register i of lane (h, g) is
-//     O[h][ (D/16)*(4*g + i) + e ].
+//     O[h][ (D/16)*(4*g + i) + e ].  (At D = 256 the 16 elements of a lane are two runs
+//     of 8, half a row apart, so that every load instruction stays contiguous.)
 //
 // P is split into a high and a low 16-bit part (P = P_hi + P_lo, two MFMAs per
 // operand) so that rounding P to the input precision never limits accuracy.
@@ -63,21 +64,20 @@ __device__ __forceinline__ void split_pair(float p0, float p1, uint32_t& hi, uin
     }
 }
 
-template <int D>
-struct VVec;
+// What one lane loads of one K or V row: kPieces pieces of kPW dwords.  Lane r of a group
+// of 16 takes bytes [256*p + r*4*kPW, +4*kPW) of the row, so that the 16 lanes of a group
+// read 64*kPW contiguous bytes per piece: 8 bytes per lane at D = 64, 16 at D = 128, and
+// two 16-byte pieces 256 bytes apart at D = 256.
+template <int PW>
+struct Piece;
 template <>
-struct VVec<128> {
+struct Piece<4> {
     using type = u32x4;
 };
 template <>
-struct VVec<64> {
+struct Piece<2> {
     using type = u32x2;
 };
-
-template <int D>
-__device__ __forceinline__ uint32_t vdword(const typename VVec<D>::type& v, int i) {
-    return v[i];
-}
 
 template <int DT, int D, int NBLK, int NW, bool DB = true>
 struct GqaCore {
@@ -87,12 +87,23 @@ struct GqaCore {
     static constexpr int kThreads = NW * 64;
     static constexpr int kTmMax = 16;
     static constexpr int kStreams = NW;
-    static constexpr int kMinWavesPerSimd = 2;
+    // at D = 256 a four-wave workgroup needs more than half of the register file per wave;
+    // it then runs as the only workgroup of its compute unit (the default launch shape anyway)
+    static constexpr int kMinWavesPerSimd = (D == 256 && NW == 4) ? 1 : 2;
     static constexpr int kKC = D / 32;          // 16-byte K pieces per lane per block
     static constexpr int kEV = D / 16;          // head-dim elements per lane per token (V side)
     static constexpr int kVW = kEV / 2;         // dwords per lane per token (V side)
-    static_assert(D == 64 || D == 128, "head dim");
-    using vvec = typename VVec<D>::type;
+    static constexpr int kPieces = D == 256 ? 2 : 1;   // loads per lane per row
+    static constexpr int kPW = kVW / kPieces;          // dwords per piece
+    static constexpr int kPE = kEV / kPieces;          // head-dim elements per piece
+    static_assert(D == 64 || D == 128 || D == 256, "head dim");
+    using pvec = typename Piece<kPW>::type;
+    struct vvec {
+        pvec p[kPieces];
+        __device__ uint32_t dword(int i) const { return p[i / kPW][i % kPW]; }
+    };
+    // head-dim index of element e (0..kEV) of the lane with row index m
+    __device__ static constexpr int col_of(int m, int e) { return (e / kPE) * (D / kPieces) + m * kPE + e % kPE; }
 
     static constexpr int kRowBytes = D * 2;
     static constexpr int kStageRow = kRowBytes + 16;                 // padded K row in LDS
@@ -124,10 +135,10 @@ struct GqaCore {
         const buffer_rsrc k_slab = make_slab(a.k + row0 * D, slab_bytes);
         const buffer_rsrc v_slab = make_slab(a.v + row0 * D, slab_bytes);
         const int k_tok = 4 * (r & 3) + (r >> 2);  // token (within a block) this lane feeds as A row r
-        // K and V: lane (r, g) loads kEV elements at column r of row 4*j + g, j = 0..3
-        const uint32_t v_lane_off = (uint32_t)(w * kCH + g) * kRowBytes + (uint32_t)r * (kEV * 2u);
+        // K and V: lane (r, g) loads its kPieces pieces of row 4*j + g, j = 0..3
+        const uint32_t v_lane_off = (uint32_t)(w * kCH + g) * kRowBytes + (uint32_t)r * (kPW * 4u);
         char* stage = reinterpret_cast<char*>(sm.area[w].k);
-        const uint32_t stage_wr = (uint32_t)g * kStageRow + (uint32_t)r * (kEV * 2u);   // + (blk*16 + 4*j) rows
+        const uint32_t stage_wr = (uint32_t)g * kStageRow + (uint32_t)r * (kPW * 4u);   // + (blk*16 + 4*j) rows
         const uint32_t stage_rd = (uint32_t)k_tok * kStageRow + (uint32_t)g * 16u;      // + blk*16 rows + 64*c2
 
         // Q^T as B operands: lane (h = r, g) holds Q[h][32*c2 + 8*g .. +8), zero rows past T_m.
@@ -150,7 +161,16 @@ struct GqaCore {
         vvec kA[NBLK][4], kB[NBLK][4];
         vvec vA[NBLK][4], vB[NBLK][4];
 
-        // Per j one fully coalesced wave-wide load of 4 rows, for K and for V.
+        auto load_row = [&](const buffer_rsrc& slab, uint32_t o) {
+            vvec x;
+#pragma unroll
+            for (int p = 0; p < kPieces; ++p) {
+                if constexpr (kPW == 4) x.p[p] = slab_load16(slab, o + 256u * p);
+                else x.p[p] = slab_load8(slab, o + 256u * p);
+            }
+            return x;
+        };
+        // Per j and piece one fully coalesced wave-wide load over 4 rows, for K and for V.
         auto load = [&](vvec(&kb)[NBLK][4], vvec(&vb)[NBLK][4], int step) {
             const uint32_t off = v_lane_off + (uint32_t)step * (kTn * kRowBytes);
 #pragma unroll
@@ -158,8 +178,7 @@ struct GqaCore {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t o = off + (uint32_t)(blk * 16 + 4 * j) * kRowBytes;
-                    if constexpr (D == 128) kb[blk][j] = slab_load16(k_slab, o);
-                    else kb[blk][j] = slab_load8(k_slab, o);
+                    kb[blk][j] = load_row(k_slab, o);
                 }
             }
 #pragma unroll
@@ -167,8 +186,7 @@ struct GqaCore {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t o = off + (uint32_t)(blk * 16 + 4 * j) * kRowBytes;
-                    if constexpr (D == 128) vb[blk][j] = slab_load16(v_slab, o);
-                    else vb[blk][j] = slab_load8(v_slab, o);
+                    vb[blk][j] = load_row(v_slab, o);
                 }
             }
         };
@@ -180,8 +198,12 @@ struct GqaCore {
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    *reinterpret_cast<vvec*>(stage + stage_wr + (uint32_t)(blk * 16 + 4 * j) * kStageRow) = kraw[blk][j];
+                for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                    for (int p = 0; p < kPieces; ++p)
+                        *reinterpret_cast<pvec*>(stage + stage_wr + (uint32_t)(blk * 16 + 4 * j) * kStageRow + 256u * p) =
+                            kraw[blk][j].p[p];
+                }
             }
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -251,8 +273,8 @@ struct GqaCore {
                 for (int e = 0; e < kEV; ++e) {
                     const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
                     uint2 va;
-                    va.x = __builtin_amdgcn_perm(vdword<D>(vb[blk][1], e >> 1), vdword<D>(vb[blk][0], e >> 1), sel);
-                    va.y = __builtin_amdgcn_perm(vdword<D>(vb[blk][3], e >> 1), vdword<D>(vb[blk][2], e >> 1), sel);
+                    va.x = __builtin_amdgcn_perm(vb[blk][1].dword(e >> 1), vb[blk][0].dword(e >> 1), sel);
+                    va.y = __builtin_amdgcn_perm(vb[blk][3].dword(e >> 1), vb[blk][2].dword(e >> 1), sel);
                     acc[e] = mfma16<DT>(va, p_hi[blk], acc[e]);
                     acc[e] = mfma16<DT>(va, p_lo[blk], acc[e]);
                 }
@@ -298,7 +320,7 @@ struct GqaCore {
 #pragma unroll
             for (int e4 = 0; e4 < kEV; e4 += 4) {
                 const f32x4 v = {acc[e4][i], acc[e4 + 1][i], acc[e4 + 2][i], acc[e4 + 3][i]};
-                *reinterpret_cast<f32x4*>(&sm.area[w].o[r][kEV * (4 * g + i) + e4]) = v;
+                *reinterpret_cast<f32x4*>(&sm.area[w].o[r][col_of(4 * g + i, e4)]) = v;
             }
         }
         if (g == 0) {

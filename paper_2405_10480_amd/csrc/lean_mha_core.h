@@ -32,7 +32,7 @@ struct MhaCore {
     static constexpr int kTmMax = 1;
     static constexpr int kStreams = NW;       // partial streams left in LDS per segment
     static constexpr int kMinWavesPerSimd = 2;
-    static_assert(D == 64 || D == 128, "head dim");
+    static_assert(D == 64 || D == 128 || D == 256, "head dim");
 
     struct alignas(16) Smem {
         float o[kStreams][kTmMax][D];

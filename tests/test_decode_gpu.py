@@ -69,7 +69,7 @@ def _mk(B, Hq, Hkv, D, dtype, seqlens, layout, seed, outlier=0.0):
 
 # ------------------------------------------------------------------ small shapes, all variants
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
-@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("D", [64, 128, 256])
 @pytest.mark.parametrize("group", [1, 2, 7, 8, 16])
 def test_small_shapes_every_kernel_variant(dtype, D, group):
     Hkv = 3
@@ -199,6 +199,21 @@ def test_every_tile_shape_and_merge_fanin(group):
         for ctas in (1, 2):
             got, got_lse, _ = _run(inp, la.Tuning(merge_fanin=fanin, ctas_per_cu=ctas))
             _check(got, got_lse, want, want_lse, f"fanin={fanin} ctas={ctas}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("group", [1, 5, 16])
+def test_head_dim_256_every_tile_shape(dtype, group):
+    # head dim 256: rows of 512 bytes, two 16-byte pieces per lane and row in the MFMA core
+    Hkv, D = 2, 256
+    seqlens = [20011, 515]
+    inp = _mk(2, Hkv * group, Hkv, D, dtype, seqlens, workloads.KV_PACKED, seed=41 + group, outlier=0.01)
+    want, want_lse = _oracle(inp)
+    for shape in range(6):
+        got, got_lse, _ = _run(inp, la.Tuning(tile_shape=shape))
+        _check(got, got_lse, want, want_lse, f"D256 {dtype} g{group} shape={shape}")
+    got, got_lse, _ = _run(inp, la.Tuning(grid=1000, merge_fanin=3))
+    _check(got, got_lse, want, want_lse, f"D256 {dtype} g{group} grid=1000")
 
 
 @pytest.mark.parametrize("group", [1, 7])

@@ -57,6 +57,12 @@ def test_grid_is_units_times_residency_and_spans_are_equal():
     assert p.grid == 4096
     p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2, grid_multiple=4)
     assert p.grid == 2048
+    # head dim 256: 1 KiB per wave-wide load is two rows, so the default LeanTile is 32 tokens
+    # for single query rows and 64 for query groups
+    p = _plan([8192], 8, 8, 256, la.BF16, la.KV_PADDED, num_cus=256)
+    assert (p.T_n, p.total_iters, p.grid) == (32, 8 * 256, 256)
+    p = _plan([8192], 16, 2, 256, la.F16, la.KV_PADDED, num_cus=256)
+    assert (p.T_n, p.T_m, p.kernel, p.total_iters) == (64, 8, 1, 2 * 128)
     # query groups use the MFMA kernel, one output tile per KV head
     p = _plan([262144], 64, 8, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2)
     assert p.kernel == 1 and p.T_m == 8 and p.num_output_tiles == 8
