@@ -57,6 +57,12 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
         ]
+        lib.oracle_attention.restype = ctypes.c_int
+        lib.oracle_attention.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int64, ctypes.c_double, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+        ]
         _lib = lib
     return _lib
 
@@ -114,6 +120,34 @@ def decode_attention(q, k, v, seqlens, *, Hq, Hkv, D, scale, kv_layout=KV_PADDED
         kv_layout, int(n_stride), float(scale), out.ctypes.data, lse.ctypes.data, int(threads))
     if rc < 0:
         raise ValueError(f"oracle_decode_attention rejected its arguments (code {rc})")
+    return (out, lse, rc) if return_threads else (out, lse)
+
+
+def attention(q, k, v, seqlens, *, N_q, Hq, Hkv, D, scale, causal, kv_layout=KV_PADDED, n_stride=0,
+              dtype=None, threads=0, return_threads=False):
+    """Exact attention of N_q query rows per sequence in fp64 (Eq. 1, one row at a time).
+
+    q ``[B,N_q,Hq,D]``; k, v as for :func:`decode_attention`.  The query rows are the last
+    N_q cached tokens; with ``causal`` row i attends to the first ``N_b - N_q + i + 1`` rows,
+    otherwise to all ``N_b``.  Returns ``(out[B,N_q,Hq,D], lse[B,N_q,Hq])``.
+    """
+    code = dtype_code_of(q) if dtype is None else dtype
+    qa, ka, va = (_as_host_array(t, code) for t in (q, k, v))
+    sl = np.ascontiguousarray(np.asarray(seqlens, dtype=np.int32))
+    B = sl.shape[0]
+    assert qa.size == B * N_q * Hq * D, "q must be [B,N_q,Hq,D]"
+    total = int(sl.sum())
+    if kv_layout == KV_PADDED:
+        assert ka.size == B * Hkv * n_stride * D and va.size == ka.size, "k/v must be [B,Hkv,n_stride,D]"
+    else:
+        assert ka.size == Hkv * total * D and va.size == ka.size, "k/v must be [Hkv,sum(seqlens),D]"
+    out = np.empty((B, N_q, Hq, D), dtype=np.float64)
+    lse = np.empty((B, N_q, Hq), dtype=np.float64)
+    rc = _load().oracle_attention(
+        qa.ctypes.data, ka.ctypes.data, va.ctypes.data, sl.ctypes.data, B, N_q, Hq, Hkv, D, code,
+        kv_layout, int(n_stride), float(scale), int(bool(causal)), out.ctypes.data, lse.ctypes.data, int(threads))
+    if rc < 0:
+        raise ValueError(f"oracle_attention rejected its arguments (code {rc})")
     return (out, lse, rc) if return_threads else (out, lse)
 
 

@@ -1,8 +1,9 @@
 /*
  * TEST INFRASTRUCTURE -- not part of the product path.
  *
- * Plain fp64 CPU definition of decode-phase softmax attention (the paper's
- * Eq. 1 in Section 2.1, with N_q = 1 as in the decode column of Table 1):
+ * Plain fp64 CPU definition of softmax attention for the decode phase (the paper's
+ * Eq. 1 in Section 2.1, with N_q = 1 as in the decode column of Table 1) and for short
+ * query tiles (N_q > 1), one query row at a time:
  *
  *     s_t  = scale * sum_j q[j] * k[t][j]          for t < N
  *     w_t  = exp(s_t - max_t s_t)
@@ -97,25 +98,33 @@ static void attend_one(const void* q, int64_t q_off, const void* k_rows, const v
 }
 
 /*
- * q   : [B, Hq, D]
+ * Query tiles (N_q >= 1 rows per sequence; Algorithm 2 counts C_m = ceil(N_q / T_m) output
+ * tiles of them).  The N_q query tokens of sequence b are its LAST N_q cached tokens.
+ *
+ * q   : [B, N_q, Hq, D]
  * k,v : PADDED [B, Hkv, n_stride, D]  (row t of (b,h) at ((b*Hkv+h)*n_stride + t)*D), or
  *       PACKED [Hkv, total, D] with total = sum(seqlens), sequence b starting at
  *       row cu[b] = sum_{b'<b} seqlens[b'] (n_stride ignored)
- * out : [B, Hq, D] doubles;  lse: [B, Hq] doubles or NULL
+ * causal = 0: every query row attends to all N_b cached rows.
+ * causal = 1: query row i (0-based) is token N_b - N_q + i of its sequence and attends to
+ *             the cached rows t <= N_b - N_q + i, i.e. to N_b - N_q + i + 1 rows.  (The paper
+ *             does not discuss masking; this is the usual decoder mask aligned to the end of
+ *             the context.)  Needs N_b >= N_q or N_b == 0.
+ * out : [B, N_q, Hq, D] doubles;  lse: [B, N_q, Hq] doubles or NULL
  * Returns the number of threads used, or a negative value for bad arguments.
  */
-int oracle_decode_attention(const void* q, const void* k, const void* v, const int32_t* seqlens,
-                            int B, int Hq, int Hkv, int D, int dtype, int kv_layout,
-                            int64_t n_stride, double scale, double* out, double* lse,
-                            int n_threads) {
+int oracle_attention(const void* q, const void* k, const void* v, const int32_t* seqlens, int B,
+                     int N_q, int Hq, int Hkv, int D, int dtype, int kv_layout, int64_t n_stride,
+                     double scale, int causal, double* out, double* lse, int n_threads) {
     if (!q || !k || !v || !seqlens || !out) return -1;
-    if (B <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv != 0) return -2;
+    if (B <= 0 || N_q <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv != 0) return -2;
     if (dtype < 0 || dtype > 2 || kv_layout < 0 || kv_layout > 1) return -3;
     int64_t total = 0, nmax = 0;
     int64_t* cu = (int64_t*)malloc((size_t)(B + 1) * sizeof(int64_t));
     if (!cu) return -4;
     for (int b = 0; b < B; ++b) {
         if (seqlens[b] < 0) { free(cu); return -5; }
+        if (causal && seqlens[b] != 0 && seqlens[b] < N_q) { free(cu); return -7; }
         cu[b] = total;
         total += seqlens[b];
         if (seqlens[b] > nmax) nmax = seqlens[b];
@@ -137,13 +146,17 @@ int oracle_decode_attention(const void* q, const void* k, const void* v, const i
 #ifdef _OPENMP
 #pragma omp for schedule(dynamic, 1)
 #endif
-        for (int64_t bh = 0; bh < (int64_t)B * Hq; ++bh) {
-            int b = (int)(bh / Hq), hq = (int)(bh % Hq), h = hq / group;
+        for (int64_t r = 0; r < (int64_t)B * N_q * Hq; ++r) {
+            int b = (int)(r / ((int64_t)N_q * Hq)), i = (int)((r / Hq) % N_q), hq = (int)(r % Hq);
+            int h;
+            h = hq / group;
             int64_t kv_off = kv_layout == ORACLE_KV_PADDED
                                  ? ((int64_t)(b * (int64_t)Hkv + h) * n_stride) * D
                                  : ((int64_t)h * total + cu[b]) * D;
-            attend_one(q, bh * D, k, v, kv_off, seqlens[b], D, dtype, scale, scores, row, qrow,
-                       out + bh * D, lse ? lse + bh : NULL);
+            int64_t n_visible = seqlens[b];
+            if (causal && n_visible > 0) n_visible = n_visible - N_q + i + 1;
+            attend_one(q, r * D, k, v, kv_off, n_visible, D, dtype, scale, scores, row, qrow,
+                       out + r * D, lse ? lse + r : NULL);
         }
         free(scores);
         free(row);
@@ -153,4 +166,16 @@ int oracle_decode_attention(const void* q, const void* k, const void* v, const i
 #endif
     free(cu);
     return used;
+}
+
+/*
+ * Decode: N_q = 1 (the mask plays no role).
+ * q   : [B, Hq, D];  out : [B, Hq, D] doubles;  lse: [B, Hq] doubles or NULL
+ */
+int oracle_decode_attention(const void* q, const void* k, const void* v, const int32_t* seqlens,
+                            int B, int Hq, int Hkv, int D, int dtype, int kv_layout,
+                            int64_t n_stride, double scale, double* out, double* lse,
+                            int n_threads) {
+    return oracle_attention(q, k, v, seqlens, B, 1, Hq, Hkv, D, dtype, kv_layout, n_stride, scale, 0,
+                            out, lse, n_threads);
 }

@@ -16,6 +16,7 @@ import oracle
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "exact_attention.c")
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_cases.json")
+QT_GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "query_tile_cases.json")
 
 MUTANTS = {
     "scale_dropped": ("scores[t] = scale * dot;", "scores[t] = dot;"),
@@ -29,6 +30,10 @@ MUTANTS = {
     "dot_misses_last_element": ("for (int j = 0; j < D; ++j) dot += qrow[j] * row[j];", "for (int j = 0; j < D - (D > 1); ++j) dot += qrow[j] * row[j];"),
     "bf16_shift_wrong": ("uint32_t u = ((uint32_t)bits) << 16;", "uint32_t u = ((uint32_t)bits) << 15;"),
     "packed_offset_ignores_sequence_start": (": ((int64_t)h * total + cu[b]) * D;", ": ((int64_t)h * total) * D;"),
+    "causal_limit_off_by_one": ("n_visible = n_visible - N_q + i + 1;", "n_visible = n_visible - N_q + i + (n_visible - N_q + i > 0 ? 0 : 1);"),
+    "causal_mask_ignores_query_row": ("n_visible = n_visible - N_q + i + 1;", "n_visible = n_visible - N_q + 1;"),
+    "query_row_and_head_transposed": ("i = (int)((r / Hq) % N_q), hq = (int)(r % Hq);",
+                                      "i = (int)(r % N_q), hq = (int)((r / N_q) % Hq);"),
     "padded_offset_ignores_head": ("? ((int64_t)(b * (int64_t)Hkv + h) * n_stride) * D", "? ((int64_t)(b * (int64_t)Hkv) * n_stride) * D"),
 }
 
@@ -44,6 +49,8 @@ def _compile(tmp_path, name, old, new):
     dll = ctypes.CDLL(lib)
     dll.oracle_decode_attention.restype = ctypes.c_int
     dll.oracle_decode_attention.argtypes = oracle._load().oracle_decode_attention.argtypes
+    dll.oracle_attention.restype = ctypes.c_int
+    dll.oracle_attention.argtypes = oracle._load().oracle_attention.argtypes
     return dll
 
 
@@ -54,6 +61,17 @@ def _call(dll, q, k, v, seqlens, Hq, Hkv, D, scale, layout, n_stride, code):
     lse = np.empty((B, Hq))
     rc = dll.oracle_decode_attention(q.ctypes.data, k.ctypes.data, v.ctypes.data, sl.ctypes.data, B, Hq, Hkv, D, code,
                                      layout, n_stride, scale, out.ctypes.data, lse.ctypes.data, 1)
+    assert rc > 0
+    return out, lse
+
+
+def _call_tile(dll, q, k, v, seqlens, N_q, Hq, Hkv, D, scale, causal, n_stride):
+    sl = np.ascontiguousarray(np.asarray(seqlens, dtype=np.int32))
+    B = len(seqlens)
+    out = np.empty((B, N_q, Hq, D))
+    lse = np.empty((B, N_q, Hq))
+    rc = dll.oracle_attention(q.ctypes.data, k.ctypes.data, v.ctypes.data, sl.ctypes.data, B, N_q, Hq, Hkv, D,
+                              oracle.F64, 0, n_stride, scale, int(causal), out.ctypes.data, lse.ctypes.data, 1)
     assert rc > 0
     return out, lse
 
@@ -95,6 +113,19 @@ def _pins_hold(dll) -> bool:
                         return False
                     if abs(lse[b, h] - (s.max() + math.log(wgt.sum()))) > 1e-12:
                         return False
+        # hand-computed query tiles (N_q = 2), causal and unmasked
+        for case in json.load(open(QT_GOLDEN))["cases"]:
+            q = np.array(case["q"], dtype=np.float64)
+            N_q, Hq = q.shape
+            k = np.log(np.array(case["k_log_of"], dtype=np.float64))
+            v = np.array(case["v"], dtype=np.float64)
+            for causal, tag in ((True, "causal"), (False, "full")):
+                out, lse = _call_tile(dll, np.ascontiguousarray(q), k, v, [k.size], N_q, Hq, case["Hkv"], 1, 1.0,
+                                      causal, k.size)
+                if np.max(np.abs(out[0, :, :, 0] - np.array(case[f"out_{tag}"]))) > 1e-12:
+                    return False
+                if np.max(np.abs(lse[0] - np.log(np.array(case[f"lse_{tag}_log_of"])))) > 1e-12:
+                    return False
         # bf16 widening: q = 1.0, one token, v carries the pattern
         bits = np.array([0x3F80, 0x4049, 0xC2F7, 0x0080, 0x3EAA], dtype=np.uint16)
         want = (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)

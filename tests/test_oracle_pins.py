@@ -381,3 +381,93 @@ def test_algorithm_2_special_cases_of_section_4_3():
     lean_alg2.lean_attention(q, k, v, [N, N], Hkv=H, T_n=T_n, G=12, scale=0.5, trace=trace)
     assert len(trace) == 12 and all(t["local_iter_end"] - t["local_iter"] == 4 for t in trace)
     assert sum(t["host"] for t in trace) == 6
+
+
+# ---------------------------------------------------------------- query tiles (N_q > 1)
+QT_GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "query_tile_cases.json")
+
+
+def _load_query_tile_cases():
+    with open(QT_GOLDEN) as fh:
+        return json.load(fh)["cases"]
+
+
+@pytest.mark.parametrize("case", _load_query_tile_cases(), ids=lambda c: c["name"])
+def test_hand_computed_query_tile_cases(case):
+    q = np.array(case["q"], dtype=np.float64)                      # [N_q, Hq]
+    N_q, Hq = q.shape
+    k = np.log(np.array(case["k_log_of"], dtype=np.float64))
+    v = np.array(case["v"], dtype=np.float64)
+    N = k.size
+    for causal, tag in ((True, "causal"), (False, "full")):
+        out, lse = oracle.attention(q.reshape(1, N_q, Hq, 1), k.reshape(1, 1, N, 1), v.reshape(1, 1, N, 1), [N],
+                                    N_q=N_q, Hq=Hq, Hkv=case["Hkv"], D=1, scale=1.0, causal=causal, n_stride=N,
+                                    dtype=oracle.F64)
+        np.testing.assert_allclose(out[0, :, :, 0], np.array(case[f"out_{tag}"]), rtol=0, atol=1e-13)
+        np.testing.assert_allclose(lse[0], np.log(np.array(case[f"lse_{tag}_log_of"])), rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("layout", [oracle.KV_PADDED, oracle.KV_PACKED])
+def test_query_tiles_against_masked_score_matrix(causal, layout):
+    # textbook form: S = scale * Q K^T with an explicit mask matrix, row softmax, P V
+    r = _rng(40 + int(causal))
+    B, N_q, Hq, Hkv, D = 4, 3, 6, 2, 5
+    lens = [7, 3, 0, 12]                      # one sequence holds exactly the N_q new tokens, one is empty
+    nmax, scale = max(lens), 0.37
+    q = r.normal(size=(B, N_q, Hq, D))
+    k = r.normal(size=(B, Hkv, nmax, D))
+    v = r.normal(size=(B, Hkv, nmax, D))
+    if layout == oracle.KV_PACKED:
+        kk = np.ascontiguousarray(np.concatenate([k[b, :, :lens[b]] for b in range(B)], axis=1))
+        vv = np.ascontiguousarray(np.concatenate([v[b, :, :lens[b]] for b in range(B)], axis=1))
+    else:
+        kk, vv = k, v
+    out, lse = oracle.attention(q, kk, vv, lens, N_q=N_q, Hq=Hq, Hkv=Hkv, D=D, scale=scale, causal=causal,
+                                kv_layout=layout, n_stride=nmax, dtype=oracle.F64)
+    group = Hq // Hkv
+    for b in range(B):
+        n = lens[b]
+        if n == 0:
+            assert np.all(out[b] == 0) and np.all(np.isneginf(lse[b]))
+            continue
+        for hq in range(Hq):
+            S = scale * q[b, :, hq] @ k[b, hq // group, :n].T            # [N_q, n]
+            if causal:
+                rows = np.arange(N_q)[:, None] + (n - N_q)
+                S = np.where(np.arange(n)[None, :] <= rows, S, -np.inf)
+            P = np.exp(S - S.max(axis=1, keepdims=True))
+            want = (P / P.sum(axis=1, keepdims=True)) @ v[b, hq // group, :n]
+            np.testing.assert_allclose(out[b, :, hq], want, rtol=0, atol=1e-13)
+            np.testing.assert_allclose(lse[b, :, hq], S.max(axis=1) + np.log(P.sum(axis=1)), rtol=0, atol=1e-13)
+
+
+def test_causal_query_rows_are_decode_steps_on_truncated_contexts():
+    # row i of a causal query tile is exactly the decode step taken when the context held
+    # N - N_q + i + 1 tokens; the last row and every row of the unmasked form see all N
+    r = _rng(42)
+    B, N_q, Hq, Hkv, D = 2, 4, 4, 2, 8
+    lens = [9, 4]
+    nmax = max(lens)
+    q = r.normal(size=(B, N_q, Hq, D))
+    k = r.normal(size=(B, Hkv, nmax, D))
+    v = r.normal(size=(B, Hkv, nmax, D))
+    kw = dict(Hq=Hq, Hkv=Hkv, D=D, scale=0.5, n_stride=nmax, dtype=oracle.F64)
+    out_c, lse_c = oracle.attention(q, k, v, lens, N_q=N_q, causal=True, **kw)
+    out_f, lse_f = oracle.attention(q, k, v, lens, N_q=N_q, causal=False, **kw)
+    for i in range(N_q):
+        step, step_lse = oracle.decode_attention(np.ascontiguousarray(q[:, i]), k, v, [n - N_q + i + 1 for n in lens], **kw)
+        assert np.array_equal(out_c[:, i], step) and np.array_equal(lse_c[:, i], step_lse)
+        full, full_lse = oracle.decode_attention(np.ascontiguousarray(q[:, i]), k, v, lens, **kw)
+        assert np.array_equal(out_f[:, i], full) and np.array_equal(lse_f[:, i], full_lse)
+    assert np.array_equal(out_c[:, -1], out_f[:, -1])
+
+
+def test_causal_query_tile_longer_than_its_context_is_rejected():
+    x = np.zeros((1, 3, 1, 2))
+    kv = np.zeros((1, 1, 2, 2))
+    with pytest.raises(ValueError):
+        oracle.attention(x, kv, kv, [2], N_q=3, Hq=1, Hkv=1, D=2, scale=1.0, causal=True, n_stride=2, dtype=oracle.F64)
+    out, _ = oracle.attention(x, kv, kv, [2], N_q=3, Hq=1, Hkv=1, D=2, scale=1.0, causal=False, n_stride=2,
+                              dtype=oracle.F64)
+    assert out.shape == (1, 3, 1, 2)
