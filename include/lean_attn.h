@@ -7,6 +7,9 @@
  *
  *     out[b,h_q,:] = softmax(scale * q[b,h_q,:] . K[b,h,:N_b,:]^T) V[b,h,:N_b,:]
  *
+ * lean_attn_attend generalises this to short query tiles (N_q > 1 rows per
+ * sequence, Algorithm 2's C_m output tiles along the query dimension).
+ *
  * The work is decomposed stream-K style (Section 4.3): the LeanTile iterations
  * of all (sequence, KV head) output tiles are laid on one line and cut into
  * equal contiguous spans, one per workgroup of a persistent grid; partial
@@ -33,18 +36,22 @@ extern "C" {
 typedef enum lean_attn_status {
     LEAN_ATTN_OK = 0,
     LEAN_ATTN_ERR_NULL_POINTER = -1,  /* a required pointer is NULL */
-    LEAN_ATTN_ERR_BAD_SHAPE = -2,     /* B, Hq, Hkv <= 0, Hq % Hkv != 0, group > 16 */
+    LEAN_ATTN_ERR_BAD_SHAPE = -2,     /* B, N_q, Hq, Hkv <= 0, Hq % Hkv != 0, too many query rows per KV head */
     LEAN_ATTN_ERR_UNSUPPORTED = -3,   /* head dim / dtype / layout not built */
     LEAN_ATTN_ERR_WORKSPACE = -4,     /* workspace missing, misaligned or too small */
-    LEAN_ATTN_ERR_SEQLEN = -5,        /* a negative length, N_b*D*2 >= 2^31 bytes, or a padded stride below the longest */
+    LEAN_ATTN_ERR_SEQLEN = -5,        /* a negative length, N_b*D*2 >= 2^31 bytes, a padded stride below the longest,
+                                         or (causal) 0 < N_b < N_q */
     LEAN_ATTN_ERR_BATCH_TOO_LARGE = -6, /* B > LEAN_ATTN_MAX_BATCH */
     LEAN_ATTN_ERR_HIP = -7,           /* a HIP runtime call failed (no device, bad stream, ...) */
     LEAN_ATTN_ERR_TUNING = -8,        /* a lean_attn_tuning field is out of range */
     LEAN_ATTN_ERR_PEER_TIMEOUT = -9   /* reported by lean_attn_workspace_status only */
 } lean_attn_status;
 
-/* Element type of q, k_cache and v_cache (the output is always fp32). */
+/* Element type of q, k_cache and v_cache. */
 typedef enum lean_attn_dtype { LEAN_ATTN_F16 = 0, LEAN_ATTN_BF16 = 1 } lean_attn_dtype;
+
+/* Element type of out: fp32, or the 16-bit type of the inputs (rounded to nearest even). */
+typedef enum lean_attn_out_dtype { LEAN_ATTN_OUT_F32 = 0, LEAN_ATTN_OUT_AS_INPUT = 1 } lean_attn_out_dtype;
 
 /*
  * KV-cache layouts.
@@ -58,29 +65,34 @@ typedef enum lean_attn_dtype { LEAN_ATTN_F16 = 0, LEAN_ATTN_BF16 = 1 } lean_attn
 typedef enum lean_attn_kv_layout { LEAN_ATTN_KV_PADDED = 0, LEAN_ATTN_KV_PACKED = 1 } lean_attn_kv_layout;
 
 #define LEAN_ATTN_MAX_BATCH 256  /* sequences per call (the schedule table travels as kernel arguments) */
-#define LEAN_ATTN_MAX_GROUP 16   /* query heads per KV head (rows of one MFMA tile) */
+#define LEAN_ATTN_MAX_TILE_ROWS 16    /* query rows of one output tile (rows of one MFMA tile) */
+#define LEAN_ATTN_MAX_QUERY_ROWS 256  /* N_q * Hq / Hkv: query rows that share one KV head */
 #define LEAN_ATTN_MAX_GRID 4096  /* upper bound on workgroups; sizes the workspace */
 
 /*
  * The stream-K schedule of one call (Section 4.3 and the first lines of
- * Algorithm 2).  Output tile = one (sequence, KV head) pair; it owns
- * ceil(N_b / T_n) LeanTile iterations.  CTA g owns iterations
+ * Algorithm 2).  The R = N_q * Hq / Hkv query rows that share a KV head (row =
+ * query token * (Hq / Hkv) + head within the group) are cut into
+ * C_m = ceil(R / 16) blocks of T_m = ceil(R / C_m) rows (the last may hold fewer).
+ * Output tile = one (sequence, KV head, row block); it owns ceil(N_b / T_n)
+ * LeanTile iterations.  CTA g owns iterations
  * [g*iters_per_cta + min(g, extra), ... + iters_per_cta + (g < extra)).
+ * For decode with up to 16 query heads per KV head, C_m = 1 and T_m = Hq / Hkv.
  */
 typedef struct lean_attn_plan {
     int32_t T_n;              /* LeanTile size in tokens */
-    int32_t T_m;              /* query rows per output tile = Hq / Hkv */
-    int32_t num_output_tiles; /* B * Hkv, including tiles of empty sequences */
+    int32_t T_m;              /* query rows per output tile */
+    int32_t num_output_tiles; /* B * Hkv * C_m, including tiles of empty sequences */
     int32_t grid;             /* G: workgroups launched, <= total_iters */
     int64_t total_iters;      /* I: LeanTile iterations over all output tiles */
     int64_t iters_per_cta;    /* floor(I / G) */
     int32_t extra;            /* I mod G: the first `extra` CTAs take one more iteration */
     int32_t block_threads;    /* workgroup size */
     int32_t max_resident;     /* compute units x workgroups resident per unit */
-    int32_t kernel;           /* 0 = VALU single-row kernel (Hq == Hkv), 1 = MFMA query-group kernel */
+    int32_t kernel;           /* 0 = VALU single-row kernel (one query row per KV head), 1 = MFMA kernel */
     int32_t fixed_split;      /* 0: stream-K spans; s >= 1: baseline schedule, s parts per output tile,
                                  CTA g = tile_idx*s + part, grid = num_output_tiles*s */
-    int32_t reserved;
+    int32_t C_m;              /* row blocks per KV head */
 } lean_attn_plan;
 
 /*
@@ -92,7 +104,7 @@ typedef struct lean_attn_tuning {
     int32_t grid;          /* force G (clipped to I and to LEAN_ATTN_MAX_GRID) */
     int32_t ctas_per_cu;   /* workgroups per compute unit used to size the default G */
     int32_t num_cus;       /* pretend the device has this many compute units (schedule queries) */
-    int32_t kernel;        /* 0 default, 1 force VALU kernel (needs Hq == Hkv), 2 force MFMA kernel */
+    int32_t kernel;        /* 0 default, 1 force VALU kernel (needs N_q * Hq == Hkv), 2 force MFMA kernel */
     int32_t xcd_remap;     /* 0 default, 1 off, 2 on: place consecutive spans on one XCD */
     int32_t spin_limit;    /* polls before a waiting CTA gives up and reports PEER_TIMEOUT */
     int32_t merge_fanin;   /* partials a CTA merges per level of the reduction tree; 0 default (8),
@@ -110,12 +122,42 @@ typedef struct lean_attn_tuning {
 } lean_attn_tuning;
 
 /*
+ * One attention problem, for lean_attn_attend and its companions.  q, out and
+ * lse are indexed [B, N_q, Hq]; the N_q query rows of a sequence are its LAST
+ * N_q cached tokens (their K/V rows are already in the cache, N_b counts them).
+ *   causal = 0: every query row attends to all N_b cached rows;
+ *   causal = 1: query row i attends to the first N_b - N_q + i + 1 cached rows
+ *               (the decoder mask, aligned to the end of the context; the paper
+ *               does not discuss masks).  Needs N_b >= N_q or N_b == 0.
+ * Every block of up to 16 query rows streams the K/V of its head once: for
+ * N_q * Hq / Hkv > 16 the K/V traffic grows by C_m.  This is a decode-phase
+ * path for short query tiles (speculative decoding, chunked prefill tails), not
+ * a prefill kernel.  Limits: N_q * Hq / Hkv <= LEAN_ATTN_MAX_QUERY_ROWS.
+ */
+typedef struct lean_attn_problem {
+    int32_t B;             /* sequences */
+    int32_t N_q;           /* query rows per sequence, >= 1 */
+    int32_t Hq;            /* query heads */
+    int32_t Hkv;           /* KV heads, divides Hq */
+    int32_t D;             /* head dim: 64, 128 or 256 */
+    int32_t dtype;         /* lean_attn_dtype of q, k_cache, v_cache */
+    int32_t out_dtype;     /* lean_attn_out_dtype */
+    int32_t kv_layout;     /* lean_attn_kv_layout */
+    int32_t causal;        /* 0 or 1 */
+    float scale;           /* multiplies q.k before the softmax */
+    int64_t kv_seq_stride; /* PADDED layout: rows between consecutive (b, h) slabs */
+} lean_attn_problem;
+
+/*
  * Bytes of device workspace lean_attn_decode needs for this problem shape:
  * arrival flags plus one partial (O~[T_m, D], m[T_m], l[T_m]) slot per CTA, as
  * in Algorithm 2 ("Op[g], mp[g], lp[g], flags[g]").  Host-only arithmetic; it
  * does not depend on the device.  Returns 0 for an unsupported shape.
  */
 size_t lean_attn_workspace_size(int B, int Hq, int Hkv, int D, int dtype);
+
+/* The same for the problem lean_attn_attend is given.  Returns 0 for an unsupported problem. */
+size_t lean_attn_problem_workspace_size(const lean_attn_problem* problem);
 
 /*
  * Clear the flags of a freshly allocated workspace (device pointer, 256-byte
@@ -141,13 +183,18 @@ int lean_attn_workspace_status(void* workspace, void* hip_stream);
 int lean_attn_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, int dtype,
                        int kv_layout, const lean_attn_tuning* tuning, lean_attn_plan* plan);
 
+/* Host-only: the schedule lean_attn_attend would use for `problem` (see lean_attn_schedule). */
+int lean_attn_problem_schedule(const lean_attn_problem* problem, const int32_t* seqlens,
+                               const lean_attn_tuning* tuning, lean_attn_plan* plan);
+
 /*
  * Host-only: the output-tile segments CTA `g` walks under `plan` (the loop of
  * Algorithm 2), computed by the same code the kernel runs.  Writes up to
  * `max_segments` records of 8 int64 each:
- *   {tile_idx, b, h_kv, local_iter, local_iter_end, host_block, finishing_block, last_cta}
- * (last_cta: the last CTA contributing to the tile; the first one is the host
- * block) and returns the number of segments, or a negative status.
+ *   {tile_idx, b, head, local_iter, local_iter_end, host_block, finishing_block, last_cta}
+ * (head = kv_head * plan->C_m + row block; last_cta: the last CTA contributing to the
+ * tile; the first one is the host block) and returns the number of segments, or a
+ * negative status.
  */
 int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, int Hkv,
                    int kv_layout, int g, int64_t* segments, int max_segments);
@@ -164,7 +211,8 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
  *   kv_seq_stride  rows between consecutive (b, h) slabs in the PADDED layout
  *   scale    multiplies q.k before the softmax (1/sqrt(D) in Eq. 1)
  *   tuning   NULL for defaults
- * Supported: D in {64, 128, 256}, both dtypes, Hq/Hkv <= 16, B <= LEAN_ATTN_MAX_BATCH.
+ * Supported: D in {64, 128, 256}, both dtypes, Hq/Hkv <= LEAN_ATTN_MAX_QUERY_ROWS,
+ * B <= LEAN_ATTN_MAX_BATCH.  Same as lean_attn_attend with N_q = 1 and fp32 output.
  * q, k_cache, v_cache and out must be 16-byte aligned.
  * The first call per device and kernel variant reads the device's unit count and the
  * kernel's residency from the runtime (cached afterwards): make it outside graph capture.
@@ -173,6 +221,21 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache,
                      const int32_t* seqlens, float* out, float* lse, void* workspace,
                      size_t workspace_bytes, int B, int Hq, int Hkv, int D, int kv_layout,
                      int64_t kv_seq_stride, float scale, int dtype, const lean_attn_tuning* tuning,
+                     void* hip_stream);
+
+/*
+ * Attention of short query tiles over the KV cache (Algorithm 2 with C_m >= 1).
+ *   problem  host, see lean_attn_problem
+ *   q        device, [B, N_q, Hq, D], 16-bit elements of problem->dtype, contiguous
+ *   k_cache, v_cache, seqlens, workspace, tuning, hip_stream  as for lean_attn_decode;
+ *            the workspace size comes from lean_attn_problem_workspace_size
+ *   out      device, [B, N_q, Hq, D], fp32 or 16-bit per problem->out_dtype
+ *   lse      device, [B, N_q, Hq] fp32, or NULL
+ * Rows of a sequence with N_b = 0 get out = 0, lse = -inf.
+ */
+int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void* k_cache,
+                     const void* v_cache, const int32_t* seqlens, void* out, float* lse,
+                     void* workspace, size_t workspace_bytes, const lean_attn_tuning* tuning,
                      void* hip_stream);
 
 /*

@@ -15,7 +15,8 @@ from . import buildlib as _build
 
 F16, BF16 = 0, 1
 KV_PADDED, KV_PACKED = 0, 1
-MAX_BATCH, MAX_GROUP, MAX_GRID = 256, 16, 4096
+OUT_F32, OUT_AS_INPUT = 0, 1
+MAX_BATCH, MAX_TILE_ROWS, MAX_QUERY_ROWS, MAX_GRID = 256, 16, 256, 4096
 
 OK = 0
 ERR_NULL_POINTER, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE = -1, -2, -3, -4
@@ -27,7 +28,17 @@ class Plan(ctypes.Structure):
         ("T_n", ctypes.c_int32), ("T_m", ctypes.c_int32), ("num_output_tiles", ctypes.c_int32),
         ("grid", ctypes.c_int32), ("total_iters", ctypes.c_int64), ("iters_per_cta", ctypes.c_int64),
         ("extra", ctypes.c_int32), ("block_threads", ctypes.c_int32), ("max_resident", ctypes.c_int32),
-        ("kernel", ctypes.c_int32), ("fixed_split", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("kernel", ctypes.c_int32), ("fixed_split", ctypes.c_int32), ("C_m", ctypes.c_int32),
+    ]
+
+
+class Problem(ctypes.Structure):
+    """``lean_attn_problem``: shape and options of one ``lean_attn_attend`` call."""
+    _fields_ = [
+        ("B", ctypes.c_int32), ("N_q", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+        ("D", ctypes.c_int32), ("dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+        ("kv_layout", ctypes.c_int32), ("causal", ctypes.c_int32), ("scale", ctypes.c_float),
+        ("kv_seq_stride", ctypes.c_int64),
     ]
 
 
@@ -75,6 +86,14 @@ def _load():
     lib.lean_attn_decode.restype = i32
     lib.lean_attn_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i32, i32, i32, i32, i32, i64,
                                      ctypes.c_float, i32, ctypes.POINTER(Tuning), vp]
+    lib.lean_attn_problem_workspace_size.restype = sz
+    lib.lean_attn_problem_workspace_size.argtypes = [ctypes.POINTER(Problem)]
+    lib.lean_attn_problem_schedule.restype = i32
+    lib.lean_attn_problem_schedule.argtypes = [ctypes.POINTER(Problem), vp, ctypes.POINTER(Tuning),
+                                               ctypes.POINTER(Plan)]
+    lib.lean_attn_attend.restype = i32
+    lib.lean_attn_attend.argtypes = [ctypes.POINTER(Problem), vp, vp, vp, vp, vp, vp, vp, sz,
+                                     ctypes.POINTER(Tuning), vp]
     lib.lean_attn_read_probe.restype = i32
     lib.lean_attn_read_probe.argtypes = [vp, sz, vp, i32, i32, vp]
     lib.lean_attn_strerror.restype = ctypes.c_char_p
@@ -190,6 +209,57 @@ def lean_attn_decode(q, k_cache, v_cache, seqlens, out, workspace, *, Hkv: int, 
         lse.data_ptr() if lse is not None else None, workspace.data_ptr(),
         workspace.numel() * workspace.element_size(), B, Hq, Hkv, D, kv_layout, int(kv_seq_stride),
         float(scale), _dtype_code(q), _tuning_ptr(tuning), _stream_handle(stream))
+    if rc != OK:
+        raise LeanAttnError(rc)
+
+
+def lean_attn_problem_workspace_size(problem: Problem) -> int:
+    return int(_load().lean_attn_problem_workspace_size(ctypes.byref(problem)))
+
+
+def lean_attn_problem_schedule(problem: Problem, seqlens, tuning: Optional[Tuning] = None) -> Plan:
+    plan = Plan()
+    if len(seqlens) != problem.B:
+        raise ValueError("seqlens must have B entries")
+    rc = _load().lean_attn_problem_schedule(ctypes.byref(problem), _seqlens_array(seqlens), _tuning_ptr(tuning),
+                                            ctypes.byref(plan))
+    if rc != OK:
+        raise LeanAttnError(rc)
+    return plan
+
+
+def lean_attn_attend(problem: Problem, q, k_cache, v_cache, seqlens, out, workspace, *, lse=None,
+                     tuning: Optional[Tuning] = None, stream=None) -> None:
+    """Launch attention of ``problem.N_q`` query rows per sequence.  Shapes as in ``lean_attn.h``."""
+    p = problem
+    if not (q.is_cuda and k_cache.is_cuda and v_cache.is_cuda and out.is_cuda and workspace.is_cuda):
+        raise ValueError("q, k_cache, v_cache, out and workspace must be device tensors")
+    if not (q.is_contiguous() and k_cache.is_contiguous() and v_cache.is_contiguous() and out.is_contiguous()):
+        raise ValueError("tensors must be contiguous")
+    n_rows = p.B * p.N_q * p.Hq
+    if q.numel() != n_rows * p.D or out.numel() != n_rows * p.D:
+        raise ValueError("q and out must be [B, N_q, Hq, D]")
+    if _dtype_code(q) != p.dtype or k_cache.dtype != q.dtype or v_cache.dtype != q.dtype:
+        raise ValueError("q, k_cache and v_cache must have the problem's element type")
+    want_out = q.dtype if p.out_dtype == OUT_AS_INPUT else "torch.float32"
+    if str(out.dtype) != str(want_out):
+        raise ValueError(f"out must have dtype {want_out}")
+    if k_cache.shape != v_cache.shape:
+        raise ValueError("k_cache and v_cache must have the same shape")
+    if len(seqlens) != p.B:
+        raise ValueError("seqlens must have B entries")
+    total = int(sum(int(x) for x in seqlens))
+    if p.kv_layout == KV_PADDED:
+        if k_cache.numel() != p.B * p.Hkv * p.kv_seq_stride * p.D:
+            raise ValueError("PADDED k_cache must be [B, Hkv, kv_seq_stride, D]")
+    elif k_cache.numel() != p.Hkv * total * p.D:
+        raise ValueError("PACKED k_cache must be [Hkv, sum(seqlens), D]")
+    if lse is not None and (str(lse.dtype) != "torch.float32" or lse.numel() != n_rows or not lse.is_cuda):
+        raise ValueError("lse must be a float32 device tensor [B, N_q, Hq]")
+    rc = _load().lean_attn_attend(
+        ctypes.byref(p), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), _seqlens_array(seqlens),
+        out.data_ptr(), lse.data_ptr() if lse is not None else None, workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), _tuning_ptr(tuning), _stream_handle(stream))
     if rc != OK:
         raise LeanAttnError(rc)
 

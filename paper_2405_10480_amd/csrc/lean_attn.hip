@@ -119,24 +119,60 @@ static int query_device(int kernel, int dtype, int D, int shape, int* cus, int* 
     return LEAN_ATTN_OK;
 }
 
-static int check_shape(int B, int Hq, int Hkv, int D, int dtype, int kv_layout) {
-    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return LEAN_ATTN_ERR_BAD_SHAPE;
-    if (Hq / Hkv > LEAN_ATTN_MAX_GROUP) return LEAN_ATTN_ERR_BAD_SHAPE;
-    if (B > LEAN_ATTN_MAX_BATCH) return LEAN_ATTN_ERR_BATCH_TOO_LARGE;
-    if (dim_index(D) < 0) return LEAN_ATTN_ERR_UNSUPPORTED;
-    if (dtype != LEAN_ATTN_F16 && dtype != LEAN_ATTN_BF16) return LEAN_ATTN_ERR_UNSUPPORTED;
-    if (kv_layout != LEAN_ATTN_KV_PADDED && kv_layout != LEAN_ATTN_KV_PACKED) return LEAN_ATTN_ERR_UNSUPPORTED;
+static int check_problem(const lean_attn_problem& p) {
+    if (p.B <= 0 || p.N_q <= 0 || p.Hq <= 0 || p.Hkv <= 0 || p.Hq % p.Hkv != 0) return LEAN_ATTN_ERR_BAD_SHAPE;
+    if ((int64_t)p.N_q * (p.Hq / p.Hkv) > LEAN_ATTN_MAX_QUERY_ROWS) return LEAN_ATTN_ERR_BAD_SHAPE;
+    if (p.causal != 0 && p.causal != 1) return LEAN_ATTN_ERR_BAD_SHAPE;
+    if (p.B > LEAN_ATTN_MAX_BATCH) return LEAN_ATTN_ERR_BATCH_TOO_LARGE;
+    if (dim_index(p.D) < 0) return LEAN_ATTN_ERR_UNSUPPORTED;
+    if (p.dtype != LEAN_ATTN_F16 && p.dtype != LEAN_ATTN_BF16) return LEAN_ATTN_ERR_UNSUPPORTED;
+    if (p.out_dtype != LEAN_ATTN_OUT_F32 && p.out_dtype != LEAN_ATTN_OUT_AS_INPUT) return LEAN_ATTN_ERR_UNSUPPORTED;
+    if (p.kv_layout != LEAN_ATTN_KV_PADDED && p.kv_layout != LEAN_ATTN_KV_PACKED) return LEAN_ATTN_ERR_UNSUPPORTED;
     return LEAN_ATTN_OK;
+}
+
+// The R = N_q * group query rows that share a KV head, cut into C_m blocks of T_m <= 16 rows
+// (Algorithm 2: C_m = ceil(N_q / T_m), with the query group folded into the rows).
+struct RowBlocks {
+    int R, C_m, T_m;
+};
+static RowBlocks row_blocks(const lean_attn_problem& p) {
+    RowBlocks rb;
+    rb.R = p.N_q * (p.Hq / p.Hkv);
+    rb.C_m = (rb.R + LEAN_ATTN_MAX_TILE_ROWS - 1) / LEAN_ATTN_MAX_TILE_ROWS;
+    rb.T_m = (rb.R + rb.C_m - 1) / rb.C_m;
+    return rb;
+}
+
+static lean_attn_problem decode_problem(int B, int Hq, int Hkv, int D, int dtype, int kv_layout,
+                                        int64_t kv_seq_stride, float scale) {
+    lean_attn_problem p;
+    std::memset(&p, 0, sizeof p);
+    p.B = B;
+    p.N_q = 1;
+    p.Hq = Hq;
+    p.Hkv = Hkv;
+    p.D = D;
+    p.dtype = dtype;
+    p.out_dtype = LEAN_ATTN_OUT_F32;
+    p.kv_layout = kv_layout;
+    p.causal = 0;
+    p.scale = scale;
+    p.kv_seq_stride = kv_seq_stride;
+    return p;
 }
 
 // The host scheduler: per-sequence tile counts, total iterations, grid, spans.
 // O(B) integer work; nothing here touches the device unless the unit count has
 // to be read.
-static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, int dtype, int kv_layout,
-                         const lean_attn_tuning* tn, lean_attn_plan* plan, Sched* sched, SchedTable* table) {
+static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, const lean_attn_tuning* tn,
+                         lean_attn_plan* plan, Sched* sched, SchedTable* table) {
     if (!seqlens || !plan) return LEAN_ATTN_ERR_NULL_POINTER;
-    int rc = check_shape(B, Hq, Hkv, D, dtype, kv_layout);
+    int rc = check_problem(p);
     if (rc != LEAN_ATTN_OK) return rc;
+    const int B = p.B, D = p.D, dtype = p.dtype, kv_layout = p.kv_layout;
+    const RowBlocks rb = row_blocks(p);
+    const int heads = p.Hkv * rb.C_m;  // output tiles per sequence
     lean_attn_tuning t;
     std::memset(&t, 0, sizeof t);
     if (tn) t = *tn;
@@ -144,10 +180,10 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
         t.xcd_remap > 2 || t.spin_limit < 0 || t.merge_fanin < 0 || t.merge_fanin == 1 || t.tile_shape < 0 ||
         t.tile_shape >= kNumShapes || t.grid_multiple < 0 || t.fixed_split < -1)
         return LEAN_ATTN_ERR_TUNING;
-    const int T_m = Hq / Hkv;
-    int kernel = T_m == 1 ? 0 : 1;
+    const int T_m = rb.T_m;
+    int kernel = rb.R == 1 ? 0 : 1;
     if (t.kernel == 1) {
-        if (T_m != 1) return LEAN_ATTN_ERR_TUNING;
+        if (rb.R != 1) return LEAN_ATTN_ERR_TUNING;
         kernel = 0;
     } else if (t.kernel == 2) {
         kernel = 1;
@@ -159,6 +195,7 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
     int64_t iters = 0, toks = 0;
     for (int b = 0; b < B; ++b) {
         if (seqlens[b] < 0) return LEAN_ATTN_ERR_SEQLEN;
+        if (p.causal && seqlens[b] != 0 && seqlens[b] < p.N_q) return LEAN_ATTN_ERR_SEQLEN;
         if (table) {
             table->cu_iters[b] = (int32_t)iters;
             table->cu_tok[b] = (int32_t)toks;
@@ -172,7 +209,7 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
         table->cu_iters[B] = (int32_t)iters;
         table->cu_tok[B] = (int32_t)toks;
     }
-    const int64_t I = iters * Hkv;
+    const int64_t I = iters * heads;
 
     int cus = t.num_cus, per_cu = t.ctas_per_cu;
     int64_t resident;
@@ -201,7 +238,7 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
     // (the behaviour the paper describes for FlashDecoding in Sections 3.3 and 6.1).
     int split = 0;
     if (t.fixed_split != 0) {
-        const int64_t tiles = (int64_t)B * Hkv;
+        const int64_t tiles = (int64_t)B * heads;
         const int64_t slots = (int64_t)cus * per_cu;
         split = t.fixed_split > 0 ? t.fixed_split : (int)(slots / tiles);
         if (split < 1) split = 1;
@@ -212,7 +249,7 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
 
     plan->T_n = T_n;
     plan->T_m = T_m;
-    plan->num_output_tiles = B * Hkv;
+    plan->num_output_tiles = B * heads;
     plan->grid = (int32_t)G;
     plan->total_iters = I;
     plan->iters_per_cta = I / G;
@@ -221,10 +258,10 @@ static int make_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, 
     plan->max_resident = (int32_t)resident;
     plan->kernel = kernel;
     plan->fixed_split = split;
-    plan->reserved = 0;
+    plan->C_m = rb.C_m;
     if (sched) {
         sched->B = B;
-        sched->Hkv = Hkv;
+        sched->Hkv = heads;
         sched->T_n = T_n;
         sched->packed = kv_layout == LEAN_ATTN_KV_PACKED;
         sched->grid = plan->grid;
@@ -243,9 +280,14 @@ using namespace lean;
 
 extern "C" {
 
+size_t lean_attn_problem_workspace_size(const lean_attn_problem* problem) {
+    if (!problem || check_problem(*problem) != LEAN_ATTN_OK) return 0;
+    return kPartialsOffset + (size_t)kMaxGrid * slot_floats(row_blocks(*problem).T_m, problem->D) * sizeof(float);
+}
+
 size_t lean_attn_workspace_size(int B, int Hq, int Hkv, int D, int dtype) {
-    if (check_shape(B, Hq, Hkv, D, dtype, LEAN_ATTN_KV_PADDED) != LEAN_ATTN_OK) return 0;
-    return kPartialsOffset + (size_t)kMaxGrid * slot_floats(Hq / Hkv, D) * sizeof(float);
+    const lean_attn_problem p = decode_problem(B, Hq, Hkv, D, dtype, LEAN_ATTN_KV_PADDED, 0, 1.f);
+    return lean_attn_problem_workspace_size(&p);
 }
 
 int lean_attn_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
@@ -275,7 +317,14 @@ int lean_attn_workspace_status(void* workspace, void* hip_stream) {
 
 int lean_attn_schedule(const int32_t* seqlens, int B, int Hq, int Hkv, int D, int dtype, int kv_layout,
                        const lean_attn_tuning* tuning, lean_attn_plan* plan) {
-    return make_schedule(seqlens, B, Hq, Hkv, D, dtype, kv_layout, tuning, plan, nullptr, nullptr);
+    const lean_attn_problem p = decode_problem(B, Hq, Hkv, D, dtype, kv_layout, 0, 1.f);
+    return make_schedule(p, seqlens, tuning, plan, nullptr, nullptr);
+}
+
+int lean_attn_problem_schedule(const lean_attn_problem* problem, const int32_t* seqlens,
+                               const lean_attn_tuning* tuning, lean_attn_plan* plan) {
+    if (!problem) return LEAN_ATTN_ERR_NULL_POINTER;
+    return make_schedule(*problem, seqlens, tuning, plan, nullptr, nullptr);
 }
 
 int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, int Hkv, int kv_layout, int g,
@@ -283,6 +332,7 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
     if (!plan || !seqlens || !segments) return LEAN_ATTN_ERR_NULL_POINTER;
     if (B <= 0 || B > LEAN_ATTN_MAX_BATCH || Hkv <= 0 || plan->T_n <= 0) return LEAN_ATTN_ERR_BAD_SHAPE;
     if (g < 0 || g >= plan->grid) return LEAN_ATTN_ERR_TUNING;
+    const int heads = Hkv * (plan->C_m > 0 ? plan->C_m : 1);
     Sched s;
     SchedTable t;
     int64_t iters = 0, toks = 0;
@@ -296,7 +346,7 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
     t.cu_iters[B] = (int32_t)iters;
     t.cu_tok[B] = (int32_t)toks;
     s.B = B;
-    s.Hkv = Hkv;
+    s.Hkv = heads;
     s.T_n = plan->T_n;
     s.packed = kv_layout == LEAN_ATTN_KV_PACKED;
     s.grid = plan->grid;
@@ -305,7 +355,7 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
     s.iters_per_cta = plan->iters_per_cta;
     s.fixed_split = plan->fixed_split;
     s.pad_ = 0;
-    if (iters * Hkv != plan->total_iters) return LEAN_ATTN_ERR_BAD_SHAPE;
+    if (iters * heads != plan->total_iters) return LEAN_ATTN_ERR_BAD_SHAPE;
     int64_t it, end;
     span_of(s, t, g, &it, &end);
     int n = 0;
@@ -328,40 +378,44 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
     return n;
 }
 
-int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache, const int32_t* seqlens, float* out,
-                     float* lse, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv, int D,
-                     int kv_layout, int64_t kv_seq_stride, float scale, int dtype, const lean_attn_tuning* tuning,
-                     void* hip_stream) {
-    if (!q || !k_cache || !v_cache || !seqlens || !out || !workspace) return LEAN_ATTN_ERR_NULL_POINTER;
-    int rc = check_shape(B, Hq, Hkv, D, dtype, kv_layout);
+int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void* k_cache, const void* v_cache,
+                     const int32_t* seqlens, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                     const lean_attn_tuning* tuning, void* hip_stream) {
+    if (!problem || !q || !k_cache || !v_cache || !seqlens || !out || !workspace) return LEAN_ATTN_ERR_NULL_POINTER;
+    const lean_attn_problem& p = *problem;
+    int rc = check_problem(p);
     if (rc != LEAN_ATTN_OK) return rc;
     if ((((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15) != 0)
         return LEAN_ATTN_ERR_BAD_SHAPE;
-    if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < lean_attn_workspace_size(B, Hq, Hkv, D, dtype))
+    if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < lean_attn_problem_workspace_size(problem))
         return LEAN_ATTN_ERR_WORKSPACE;
+    const int B = p.B, D = p.D;
 
     lean_attn_plan plan;
     DecodeArgs a;
-    rc = make_schedule(seqlens, B, Hq, Hkv, D, dtype, kv_layout, tuning, &plan, &a.sched, &a.table);
+    rc = make_schedule(p, seqlens, tuning, &plan, &a.sched, &a.table);
     if (rc != LEAN_ATTN_OK) return rc;
     int32_t longest = 0, has_empty = 0;
     for (int b = 0; b < B; ++b) {
         if (seqlens[b] > longest) longest = seqlens[b];
         if (seqlens[b] == 0) has_empty = 1;
     }
-    if (kv_layout == LEAN_ATTN_KV_PADDED && kv_seq_stride < longest) return LEAN_ATTN_ERR_SEQLEN;
+    if (p.kv_layout == LEAN_ATTN_KV_PADDED && p.kv_seq_stride < longest) return LEAN_ATTN_ERR_SEQLEN;
 
     hipStream_t stream = (hipStream_t)hip_stream;
+    const int out16 = p.out_dtype == LEAN_ATTN_OUT_AS_INPUT;
     if (plan.total_iters == 0) {  // every sequence is empty
-        const int64_t rows = (int64_t)B * Hq;
-        hipLaunchKernelGGL(lean_zero_rows_kernel, dim3((unsigned)((rows * D + 255) / 256)), dim3(256), 0, stream, out,
-                           lse, rows, D);
+        const int64_t rows = (int64_t)B * p.N_q * p.Hq;
+        const int row_words = out16 ? D / 2 : D;
+        hipLaunchKernelGGL(lean_zero_rows_kernel, dim3((unsigned)((rows * row_words + 255) / 256)), dim3(256), 0,
+                           stream, (uint32_t*)out, lse, rows, row_words);
         return hipGetLastError() == hipSuccess ? LEAN_ATTN_OK : LEAN_ATTN_ERR_HIP;
     }
 
     Variant var;
-    if (!pick_variant(plan.kernel, dtype, D, tuning ? tuning->tile_shape : 0, &var)) return LEAN_ATTN_ERR_UNSUPPORTED;
+    if (!pick_variant(plan.kernel, p.dtype, D, tuning ? tuning->tile_shape : 0, &var)) return LEAN_ATTN_ERR_UNSUPPORTED;
 
+    const RowBlocks rb = row_blocks(p);
     a.q = (const uint16_t*)q;
     a.k = (const uint16_t*)k_cache;
     a.v = (const uint16_t*)v_cache;
@@ -370,18 +424,25 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache, co
     a.status = (uint32_t*)workspace;
     a.flags = (uint32_t*)((char*)workspace + kFlagsOffset);
     a.partials = (float*)((char*)workspace + kPartialsOffset);
-    a.kv_seq_stride = kv_seq_stride;
+    a.kv_seq_stride = p.kv_seq_stride;
     a.total_rows = a.table.cu_tok[B];
-    a.Hq = Hq;
-    a.T_m = plan.T_m;
-    a.slot = slot_floats(plan.T_m, D);
+    a.Hq = p.Hq;
+    a.Hkv = p.Hkv;
+    a.N_q = p.N_q;
+    a.group = p.Hq / p.Hkv;
+    a.rows = rb.R;
+    a.C_m = rb.C_m;
+    a.T_m = rb.T_m;
+    a.causal = p.causal;
+    a.out16 = out16;
+    a.slot = slot_floats(rb.T_m, D);
     // the remap permutes span ids against dispatch order: only safe while the whole grid is resident
     a.xcd_remap = (tuning && tuning->xcd_remap == 2 && plan.grid <= plan.max_resident) ? 1 : 0;
     a.spin_limit = (tuning && tuning->spin_limit > 0) ? tuning->spin_limit : (1 << 22);
     a.has_empty = has_empty;
     a.fanin = (tuning && tuning->merge_fanin >= 2) ? tuning->merge_fanin : kDefaultFanin;
     a.cta_clock = tuning ? (unsigned long long*)tuning->cta_clock : nullptr;
-    a.scale_log2e = scale * 1.4426950408889634f;
+    a.scale_log2e = p.scale * 1.4426950408889634f;
 
     void* params[] = {&a};
     if (hipLaunchKernel(var.fn, dim3(plan.grid), dim3(var.threads), params, 0, stream) != hipSuccess) {
@@ -389,6 +450,15 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache, co
         return LEAN_ATTN_ERR_HIP;
     }
     return LEAN_ATTN_OK;
+}
+
+int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache, const int32_t* seqlens, float* out,
+                     float* lse, void* workspace, size_t workspace_bytes, int B, int Hq, int Hkv, int D,
+                     int kv_layout, int64_t kv_seq_stride, float scale, int dtype, const lean_attn_tuning* tuning,
+                     void* hip_stream) {
+    const lean_attn_problem p = decode_problem(B, Hq, Hkv, D, dtype, kv_layout, kv_seq_stride, scale);
+    return lean_attn_attend(&p, q, k_cache, v_cache, seqlens, out, lse, workspace, workspace_bytes, tuning,
+                            hip_stream);
 }
 
 int lean_attn_read_probe(const void* buf, size_t bytes, void* sink, int grid, int mode, void* hip_stream) {
@@ -405,7 +475,7 @@ const char* lean_attn_strerror(int status) {
     switch (status) {
         case LEAN_ATTN_OK: return "ok";
         case LEAN_ATTN_ERR_NULL_POINTER: return "a required pointer is null";
-        case LEAN_ATTN_ERR_BAD_SHAPE: return "bad shape: B, Hq, Hkv must be positive, Hq a multiple of Hkv with group <= 16, 16-byte aligned tensors";
+        case LEAN_ATTN_ERR_BAD_SHAPE: return "bad shape: B, N_q, Hq, Hkv must be positive, Hq a multiple of Hkv, at most 256 query rows per KV head, 16-byte aligned tensors";
         case LEAN_ATTN_ERR_UNSUPPORTED: return "unsupported head dim (64, 128), dtype (f16, bf16) or layout";
         case LEAN_ATTN_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or smaller than lean_attn_workspace_size";
         case LEAN_ATTN_ERR_SEQLEN: return "negative sequence length, padded stride below the longest sequence, or more than 2^31 tokens";

@@ -27,15 +27,22 @@ struct DecodeArgs {
     const uint16_t* q;
     const uint16_t* k;
     const uint16_t* v;
-    float* out;
-    float* lse;            // may be null
+    void* out;             // [B, N_q, Hq, D], fp32 or (out16) the element type of q
+    float* lse;            // [B, N_q, Hq], may be null
     uint32_t* status;      // workspace + 0
     uint32_t* flags;       // workspace + kFlagsOffset
     float* partials;       // workspace + kPartialsOffset
     int64_t kv_seq_stride; // PADDED: rows between (b,h) slabs
     int64_t total_rows;    // PACKED: sum of N_b
     int32_t Hq;
-    int32_t T_m;           // Hq / Hkv
+    int32_t Hkv;           // KV heads (the schedule counts Hkv * C_m output tiles per sequence)
+    int32_t N_q;           // query tokens per sequence: the last N_q cached tokens
+    int32_t group;         // Hq / Hkv
+    int32_t rows;          // N_q * group query rows share one KV head; row rho = token*group + head
+    int32_t C_m;           // row blocks per KV head, ceil(rows / 16)
+    int32_t T_m;           // rows per block, ceil(rows / C_m); the last block may hold fewer
+    int32_t causal;        // row of query token i sees the first N_b - N_q + i + 1 cached tokens
+    int32_t out16;         // out holds 16-bit elements
     int32_t slot;          // floats per partial slot
     int32_t xcd_remap;
     int32_t spin_limit;
@@ -47,6 +54,26 @@ struct DecodeArgs {
     SchedTable table;
 };
 
+// The rows of output tile (b, head) where head = hk * C_m + mb: KV head hk, row block mb.
+struct TileRows {
+    int hk;     // KV head
+    int rho0;   // first row of the block within the KV head's rows
+    int count;  // rows in the block
+};
+__device__ __forceinline__ TileRows tile_rows(const DecodeArgs& a, int head) {
+    TileRows t;
+    t.hk = a.C_m == 1 ? head : head / a.C_m;
+    t.rho0 = (head - t.hk * a.C_m) * a.T_m;
+    t.count = a.rows - t.rho0 < a.T_m ? a.rows - t.rho0 : a.T_m;
+    return t;
+}
+// Index into q / out / lse rows ([B, N_q, Hq]) of row rho of KV head hk; *token gets the query token.
+__device__ __forceinline__ int64_t query_row(const DecodeArgs& a, int b, int hk, int rho, int* token) {
+    const int i = a.N_q == 1 ? 0 : rho / a.group;
+    *token = i;
+    return ((int64_t)b * a.N_q + i) * a.Hq + (int64_t)hk * a.group + (rho - i * a.group);
+}
+
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
@@ -57,6 +84,18 @@ __device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
 
 // The two 16-bit elements packed in one dword, widened to fp32 (low half first).
+// Two fp32 values rounded to nearest-even 16-bit elements, packed low half first.
+template <int DT>
+__device__ __forceinline__ uint32_t narrow2(float lo, float hi) {
+    if constexpr (DT == kDtBF16) {
+        const bf16x2 p = {(__bf16)lo, (__bf16)hi};
+        return __builtin_bit_cast(uint32_t, p);
+    } else {
+        const f16x2 p = {(_Float16)lo, (_Float16)hi};
+        return __builtin_bit_cast(uint32_t, p);
+    }
+}
+
 template <int DT>
 __device__ __forceinline__ void widen2(uint32_t u, float& lo, float& hi) {
     if constexpr (DT == kDtBF16) {

@@ -82,6 +82,7 @@ struct Piece<2> {
 template <int DT, int D, int NBLK, int NW, bool DB = true>
 struct GqaCore {
     static constexpr int kD = D;
+    static constexpr int kDT = DT;
     static constexpr int kTn = NW * NBLK * 16;  // LeanTile
     static constexpr int kCH = NBLK * 16;       // tokens per wave per step
     static constexpr int kThreads = NW * 64;
@@ -126,11 +127,11 @@ struct GqaCore {
         const int r = lane & 15;   // A row / B column index of the lane
         const int g = lane >> 4;   // k-group of the lane
         const int n_ctx = sg.n_ctx;
-        const int T_m = a.T_m;
+        const TileRows tr = tile_rows(a, sg.h);
 
         const int64_t row0 = a.sched.packed
-                                 ? (int64_t)sg.h * a.total_rows + a.table.cu_tok[sg.b]
-                                 : ((int64_t)sg.b * a.sched.Hkv + sg.h) * a.kv_seq_stride;
+                                 ? (int64_t)tr.hk * a.total_rows + a.table.cu_tok[sg.b]
+                                 : ((int64_t)sg.b * a.Hkv + tr.hk) * a.kv_seq_stride;
         const uint32_t slab_bytes = (uint32_t)n_ctx * kRowBytes;
         const buffer_rsrc k_slab = make_slab(a.k + row0 * D, slab_bytes);
         const buffer_rsrc v_slab = make_slab(a.v + row0 * D, slab_bytes);
@@ -141,13 +142,17 @@ struct GqaCore {
         const uint32_t stage_wr = (uint32_t)g * kStageRow + (uint32_t)r * (kPW * 4u);   // + (blk*16 + 4*j) rows
         const uint32_t stage_rd = (uint32_t)k_tok * kStageRow + (uint32_t)g * 16u;      // + blk*16 rows + 64*c2
 
-        // Q^T as B operands: lane (h = r, g) holds Q[h][32*c2 + 8*g .. +8), zero rows past T_m.
+        // Q^T as B operands: lane (row r, g) holds Q[r][32*c2 + 8*g .. +8), zero rows past the block.
+        // n_vis: cached tokens the lane's query row may attend to (causal mask aligned to the end).
         u32x4 qb[kKC];
 #pragma unroll
         for (int c2 = 0; c2 < kKC; ++c2) qb[c2] = u32x4{0u, 0u, 0u, 0u};
-        if (r < T_m) {
-            const u32x4* qp =
-                reinterpret_cast<const u32x4*>(a.q + ((int64_t)sg.b * a.Hq + (int64_t)sg.h * T_m + r) * D) + g;
+        int n_vis = n_ctx;
+        if (r < tr.count) {
+            int token;
+            const int64_t qrow = query_row(a, sg.b, tr.hk, tr.rho0 + r, &token);
+            if (a.causal) n_vis = n_ctx - a.N_q + token + 1;
+            const u32x4* qp = reinterpret_cast<const u32x4*>(a.q + qrow * D) + g;
 #pragma unroll
             for (int c2 = 0; c2 < kKC; ++c2) qb[c2] = qp[4 * c2];
         }
@@ -228,7 +233,7 @@ struct GqaCore {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     float x = c[i] * a.scale_log2e;
-                    if (base + blk * 16 + 4 * i + g >= n_ctx) x = -INFINITY;  // masked tail tokens
+                    if (base + blk * 16 + 4 * i + g >= n_vis) x = -INFINITY;  // tail and masked tokens
                     c[i] = x;
                     mx = fmaxf(mx, x);
                 }

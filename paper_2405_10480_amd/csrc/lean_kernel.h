@@ -113,15 +113,23 @@ __device__ __forceinline__ void reduce_tile(const DecodeArgs& a, OwnPartial<CPT>
         signal_arrival(a.flags + g);
     } else {
         // m is kept in the base-2 domain: L = ln2 * (m + log2 l)
-        const int64_t out_row0 = (int64_t)b * a.Hq + (int64_t)h * T_m;
+        const TileRows tr = tile_rows(a, h);
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
             const int c = tid + i * THREADS;
-            if (c < n_chunks) {
-                const float inv = 1.f / own.l[i];
-                *reinterpret_cast<f32x4*>(a.out + out_row0 * D + 4 * c) = own.o[i] * inv;
-                if (a.lse && (4 * c) % D == 0)
-                    a.lse[out_row0 + (4 * c) / D] = 0.6931471805599453f * (own.m[i] + __builtin_amdgcn_logf(own.l[i]));
+            const int row = (4 * c) / D, col = (4 * c) % D;
+            if (c < n_chunks && row < tr.count) {
+                int token;
+                const int64_t orow = query_row(a, b, tr.hk, tr.rho0 + row, &token);
+                const f32x4 o = own.o[i] * (1.f / own.l[i]);
+                if (a.out16) {
+                    *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(a.out) + orow * D + col) =
+                        u32x2{narrow2<Core::kDT>(o.x, o.y), narrow2<Core::kDT>(o.z, o.w)};
+                } else {
+                    *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + orow * D + col) = o;
+                }
+                if (a.lse && col == 0)
+                    a.lse[orow] = 0.6931471805599453f * (own.m[i] + __builtin_amdgcn_logf(own.l[i]));
             }
         }
     }
@@ -154,10 +162,13 @@ __global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_d
     stamp(a, g, 0);
 
     if (a.has_empty) {  // sequences with N_b = 0 own no iteration: their rows are defined as zero
-        for (int row = g; row < a.sched.B * a.Hq; row += G) {
-            const int b = row / a.Hq;
+        const int rows_per_seq = a.N_q * a.Hq;
+        const int row_words = a.out16 ? D / 2 : D;  // zero bits are 0.0 in every output type
+        for (int row = g; row < a.sched.B * rows_per_seq; row += G) {
+            const int b = row / rows_per_seq;
             if (a.table.cu_tok[b + 1] == a.table.cu_tok[b]) {
-                for (int c = tid; c < D; c += THREADS) a.out[(int64_t)row * D + c] = 0.f;
+                for (int c = tid; c < row_words; c += THREADS)
+                    reinterpret_cast<uint32_t*>(a.out)[(int64_t)row * row_words + c] = 0u;
                 if (a.lse && tid == 0) a.lse[row] = -INFINITY;
             }
         }
@@ -239,9 +250,9 @@ __global__ void lean_workspace_clear_kernel(uint32_t* words, int n) {
 }
 
 // All sequences empty: only zeros to write.
-__global__ void lean_zero_rows_kernel(float* out, float* lse, int64_t rows, int D) {
+__global__ void lean_zero_rows_kernel(uint32_t* out_words, float* lse, int64_t rows, int row_words) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < rows * D) out[i] = 0.f;
+    if (i < rows * row_words) out_words[i] = 0u;
     if (lse && i < rows) lse[i] = -INFINITY;
 }
 

@@ -24,6 +24,7 @@ namespace lean {
 template <int DT, int D, int U, int NW, bool DB = true>
 struct MhaCore {
     static constexpr int kD = D;
+    static constexpr int kDT = DT;
     static constexpr int kLPR = D / 8;        // lanes per row
     static constexpr int kRPI = 64 / kLPR;    // rows per wave-wide load
     static constexpr int kCH = U * kRPI;      // tokens per wave per step
@@ -53,7 +54,7 @@ struct MhaCore {
 
         const int64_t row0 = a.sched.packed
                                  ? (int64_t)sg.h * a.total_rows + a.table.cu_tok[sg.b]
-                                 : ((int64_t)sg.b * a.sched.Hkv + sg.h) * a.kv_seq_stride;
+                                 : ((int64_t)sg.b * a.Hkv + sg.h) * a.kv_seq_stride;
         constexpr uint32_t kRowBytes = D * 2;
         const uint32_t slab_bytes = (uint32_t)n_ctx * kRowBytes;
         const buffer_rsrc k_slab = make_slab(a.k + row0 * D, slab_bytes);

@@ -2,8 +2,10 @@
 // of Algorithm 2), shared by the host scheduler and the device span walk so
 // that both run literally the same index arithmetic.
 //
-// Output tile  = one (sequence b, KV head h) pair; it owns C_n[b] = ceil(N_b / T_n)
-//                LeanTile iterations.
+// Output tile  = one (sequence b, head h) pair; it owns C_n[b] = ceil(N_b / T_n)
+//                LeanTile iterations.  With up to 16 query rows per KV head, h is the KV
+//                head; with more, the rows are cut into C_m blocks and h = kv_head*C_m + block
+//                (Algorithm 2's C_m output tiles along the query dimension).
 // Linearization: PADDED cache  b -> h -> context   (iter = Hkv*cuC[b] + h*C_n[b] + local)
 //                PACKED cache  h -> b -> context   (iter = h*cuC[B] + cuC[b] + local)
 //                (the paper's "batch -> heads -> context" and, for ragged
@@ -36,7 +38,7 @@ struct SchedTable {
 
 struct Sched {
     int32_t B;
-    int32_t Hkv;
+    int32_t Hkv;            // output tiles per sequence: KV heads x row blocks per KV head (C_m)
     int32_t T_n;
     int32_t packed;         // 0: PADDED order b->h->t, 1: PACKED order h->b->t
     int32_t grid;           // G

@@ -325,3 +325,136 @@ def test_ragged_batch_full_size_sampled_heads():
                                                  kv_layout=oracle.KV_PACKED)
         _check(got[:, h:h + 1], got_lse[:, h:h + 1], want, want_lse, f"{w.name} head {h}")
         del sub
+
+
+# ------------------------------------------------------------------ query tiles (N_q > 1), row blocks, 16-bit out
+def _mk_tile(B, N_q, Hq, Hkv, D, dtype, seqlens, layout, seed, causal, outlier=0.0):
+    w = workloads.Workload(f"t_b{B}_q{N_q}_h{Hq}_{Hkv}_d{D}_{dtype}", B, Hq, Hkv, D, dtype, tuple(seqlens), layout,
+                           seed=seed, outlier_frac=outlier, N_q=N_q, causal=causal)
+    return workloads.generate(w, device="cuda")
+
+
+def _problem_of(w, out_dtype=la.OUT_F32):
+    return la.Problem(B=w.B, N_q=w.N_q, Hq=w.Hq, Hkv=w.Hkv, D=w.D, dtype=la.F16 if w.dtype == "f16" else la.BF16,
+                      out_dtype=out_dtype, kv_layout=w.kv_layout, causal=int(w.causal), scale=w.scale,
+                      kv_seq_stride=w.n_stride)
+
+
+def _run_attend(inp, tuning=None, out_dtype=la.OUT_F32, want_lse=True):
+    w = inp.w
+    pr = _problem_of(w, out_dtype)
+    ws = torch.empty(la.lean_attn_problem_workspace_size(pr), dtype=torch.uint8, device="cuda")
+    la.lean_attn_workspace_init(ws)
+    odt = torch.float32 if out_dtype == la.OUT_F32 else w.torch_dtype
+    out = torch.full((w.B, w.N_q, w.Hq, w.D), float("nan"), dtype=odt, device="cuda")
+    lse = torch.full((w.B, w.N_q, w.Hq), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
+    la.lean_attn_attend(pr, inp.q, inp.k, inp.v, inp.seqlens, out, ws, lse=lse, tuning=tuning)
+    torch.cuda.synchronize()
+    assert la.lean_attn_workspace_status(ws) == 0
+    return out, (lse.cpu().numpy() if want_lse else None)
+
+
+def _oracle_attend(inp):
+    w = inp.w
+    return oracle.attention(inp.q, inp.k, inp.v, inp.seqlens, N_q=w.N_q, Hq=w.Hq, Hkv=w.Hkv, D=w.D, scale=w.scale,
+                            causal=w.causal, kv_layout=w.kv_layout, n_stride=w.n_stride)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("D", [64, 128, 256])
+@pytest.mark.parametrize("N_q,group", [(2, 1), (4, 4), (16, 1), (3, 8), (5, 7), (1, 17), (1, 32), (16, 16)])
+def test_query_tiles_and_row_blocks_small_shapes(causal, D, N_q, group):
+    # rows per KV head from 2 to 256: one block, several blocks, a ragged last block
+    Hkv = 2
+    seqlens = [1000, N_q, 0, 257, 64 + N_q]      # one sequence holds only its query tokens, one is empty
+    dtype = "bf16" if (N_q + group) % 2 else "f16"
+    for layout in (workloads.KV_PADDED, workloads.KV_PACKED):
+        inp = _mk_tile(len(seqlens), N_q, Hkv * group, Hkv, D, dtype, seqlens, layout, seed=50 + N_q + group,
+                       causal=causal)
+        want, want_lse = _oracle_attend(inp)
+        got, got_lse = _run_attend(inp)
+        _check(got.cpu().numpy(), got_lse, want, want_lse, f"N_q={N_q} g={group} D={D} causal={causal} l={layout}")
+        assert np.all(got[2].cpu().numpy() == 0.0) and np.all(np.isneginf(got_lse[2]))
+
+
+@pytest.mark.parametrize("N_q,group", [(4, 4), (6, 8)])
+def test_query_tiles_deep_trees_any_split_and_tile_shape(N_q, group):
+    Hkv, D = 2, 128
+    seqlens = [50001, 4099]
+    inp = _mk_tile(2, N_q, Hkv * group, Hkv, D, "bf16", seqlens, workloads.KV_PADDED, seed=61, causal=True,
+                   outlier=0.01)
+    want, want_lse = _oracle_attend(inp)
+    for tn in (la.Tuning(), la.Tuning(grid=3), la.Tuning(grid=1000, merge_fanin=3), la.Tuning(fixed_split=5),
+               la.Tuning(tile_shape=1), la.Tuning(tile_shape=4), la.Tuning(tile_shape=5, ctas_per_cu=2)):
+        got, got_lse = _run_attend(inp, tn)
+        _check(got.cpu().numpy(), got_lse, want, want_lse, f"N_q={N_q} g={group} grid={tn.grid} shape={tn.tile_shape}")
+
+
+def test_causal_last_row_equals_plain_decode():
+    # the last query row sees the whole context: same rows as a decode call on the same cache
+    Hkv, group, D, N_q = 2, 4, 128, 4
+    inp = _mk_tile(1, N_q, Hkv * group, Hkv, D, "bf16", [9000], workloads.KV_PADDED, seed=63, causal=True)
+    got, _ = _run_attend(inp)
+    w = inp.w
+    out = torch.empty(1, w.Hq, D, dtype=torch.float32, device="cuda")
+    ws = _workspace(1, w.Hq, Hkv, D, la.BF16)
+    la.lean_attn_decode(inp.q[:, -1].contiguous(), inp.k, inp.v, inp.seqlens, out, ws, Hkv=Hkv,
+                        kv_seq_stride=w.n_stride, scale=w.scale)
+    torch.cuda.synchronize()
+    assert torch.max(torch.abs(out - got[:, -1])).item() < 2e-6
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("N_q,group", [(1, 1), (1, 8), (3, 8)])
+def test_sixteen_bit_output_is_the_rounded_fp32_output(dtype, N_q, group):
+    Hkv, D = 3, 128
+    seqlens = [3000, 0, 129 + N_q]
+    inp = _mk_tile(3, N_q, Hkv * group, Hkv, D, dtype, seqlens, workloads.KV_PACKED, seed=70 + group, causal=N_q > 1)
+    want, want_lse = _oracle_attend(inp)
+    out32, lse32 = _run_attend(inp)
+    out16, lse16 = _run_attend(inp, out_dtype=la.OUT_AS_INPUT)
+    assert out16.dtype == inp.w.torch_dtype
+    # same kernel, same arithmetic: the 16-bit result is the fp32 result rounded to nearest even
+    assert torch.equal(out16, out32.to(out16.dtype))
+    assert np.array_equal(lse16, lse32, equal_nan=True)
+    # against the oracle: half an ulp of the output type on top of the fp32 bar
+    half_ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -11      # relative, 8 and 11 significand bits
+    err = np.abs(out16.float().cpu().numpy() - want)
+    assert np.all(err <= TIGHT_ABS + half_ulp * np.abs(want) * 1.01 + 1e-7)
+    assert np.all(out16[1].float().cpu().numpy() == 0.0)
+
+
+def test_all_sequences_empty_with_query_tiles_and_sixteen_bit_output():
+    inp = _mk_tile(2, 3, 4, 2, 64, "f16", [0, 0], workloads.KV_PADDED, seed=80, causal=True)
+    # a PADDED cache whose rows are never read (a stride of 0 would leave no memory to point at)
+    pr = _problem_of(inp.w, la.OUT_AS_INPUT)
+    pr.kv_seq_stride = 4
+    kv = torch.zeros(2, 2, 4, 64, dtype=torch.float16, device="cuda")
+    ws = torch.empty(la.lean_attn_problem_workspace_size(pr), dtype=torch.uint8, device="cuda")
+    la.lean_attn_workspace_init(ws)
+    out = torch.full((2, 3, 4, 64), float("nan"), dtype=torch.float16, device="cuda")
+    lse = torch.full((2, 3, 4), float("nan"), dtype=torch.float32, device="cuda")
+    la.lean_attn_attend(pr, inp.q, kv, kv, [0, 0], out, ws, lse=lse)
+    torch.cuda.synchronize()
+    assert torch.all(out == 0) and torch.all(torch.isneginf(lse))
+
+
+def test_attend_error_paths():
+    inp = _mk_tile(1, 4, 4, 2, 128, "bf16", [100], workloads.KV_PADDED, seed=81, causal=True)
+    pr = _problem_of(inp.w)
+    ws = torch.empty(la.lean_attn_problem_workspace_size(pr), dtype=torch.uint8, device="cuda")
+    la.lean_attn_workspace_init(ws)
+    out = torch.zeros(1, 4, 4, 128, device="cuda")
+    with pytest.raises(la.LeanAttnError) as e:       # causal with fewer cached tokens than query rows
+        la.lean_attn_attend(pr, inp.q, inp.k, inp.v, [3], out, ws)
+    assert e.value.status == la.binding.ERR_SEQLEN
+    with pytest.raises(la.LeanAttnError) as e:       # workspace sized for a smaller tile
+        small = torch.empty(la.lean_attn_workspace_size(1, 2, 2, 128, la.BF16), dtype=torch.uint8, device="cuda")
+        la.lean_attn_attend(pr, inp.q, inp.k, inp.v, [100], out, small)
+    assert e.value.status == la.binding.ERR_WORKSPACE
+    with pytest.raises(ValueError):                  # out dtype must match the problem
+        la.lean_attn_attend(pr, inp.q, inp.k, inp.v, [100], out.to(torch.bfloat16), ws)
+    la.lean_attn_attend(pr, inp.q, inp.k, inp.v, [100], out, ws)
+    torch.cuda.synchronize()
+    want, _ = _oracle_attend(inp)
+    _check(out.cpu().numpy(), None, want, None, "after errors")

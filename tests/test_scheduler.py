@@ -25,7 +25,8 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(lean_attn_[a-z_]+)\s*\(", header))
     assert {"lean_attn_decode", "lean_attn_workspace_size", "lean_attn_schedule", "lean_attn_walk",
             "lean_attn_workspace_init", "lean_attn_workspace_status", "lean_attn_read_probe",
-            "lean_attn_strerror"} <= names
+            "lean_attn_strerror", "lean_attn_attend", "lean_attn_problem_schedule",
+            "lean_attn_problem_workspace_size"} <= names
     lib = ctypes.CDLL(la.library_path())
     for n in names:
         assert hasattr(lib, n), f"{n} declared in lean_attn.h but not exported"
@@ -96,6 +97,7 @@ def test_walk_matches_the_step_by_step_emulation_of_algorithm_2(G):
 def _check_invariants(seqlens, Hkv, layout, p):
     """Coverage, one host per tile, at most one published partial per CTA, exact peer ranges."""
     C = [math.ceil(n / p.T_n) for n in seqlens]
+    heads = Hkv * max(1, p.C_m)          # output tiles per sequence: KV heads x row blocks
     covered = {}
     hosts = {}
     contributors = {}
@@ -115,10 +117,10 @@ def _check_invariants(seqlens, Hkv, layout, p):
             else:
                 assert i == 0, "only a CTA's first segment can start mid-tile: one workspace slot per CTA"
             assert bool(s["finishing"]) == (s["local_iter_end"] == C[s["b"]])
-            expect_idx = s["b"] * Hkv + s["h"] if layout == la.KV_PADDED else s["h"] * len(seqlens) + s["b"]
+            expect_idx = s["b"] * heads + s["h"] if layout == la.KV_PADDED else s["h"] * len(seqlens) + s["b"]
             assert s["tile_idx"] == expect_idx
     for b, n in enumerate(seqlens):
-        for h in range(Hkv):
+        for h in range(heads):
             if C[b] == 0:
                 assert (b, h) not in covered
                 continue
@@ -138,6 +140,64 @@ def test_span_invariants_ragged(layout, G):
     seqlens = [1024, 131072, 5000, 0, 77, 128, 129, 40000]
     p = _plan(seqlens, 4, 4, 128, la.BF16, layout, num_cus=G, ctas_per_cu=1, grid=G)
     _check_invariants(seqlens, 4, layout, p)
+
+
+def _problem(B, N_q, Hq, Hkv, D, dtype=la.BF16, layout=la.KV_PADDED, causal=0, out_dtype=la.OUT_F32, stride=0):
+    return la.Problem(B=B, N_q=N_q, Hq=Hq, Hkv=Hkv, D=D, dtype=dtype, out_dtype=out_dtype, kv_layout=layout,
+                      causal=causal, scale=1.0, kv_seq_stride=stride)
+
+
+def test_query_rows_are_cut_into_row_blocks():
+    # Algorithm 2: C_m output tiles along the query dimension; the query group is folded into the rows
+    tn = la.Tuning(num_cus=256)
+    cases = [  # N_q, Hq, Hkv -> R, C_m, T_m, kernel
+        (1, 8, 8, 1, 1, 1, 0), (1, 64, 8, 8, 1, 8, 1), (1, 64, 2, 32, 2, 16, 1), (1, 34, 2, 17, 2, 9, 1),
+        (4, 8, 8, 4, 1, 4, 1), (3, 16, 2, 24, 2, 12, 1), (16, 32, 2, 256, 16, 16, 1), (5, 28, 4, 35, 3, 12, 1),
+    ]
+    seqlens = [5000, 0, 777]
+    for N_q, Hq, Hkv, R, C_m, T_m, kernel in cases:
+        pr = _problem(3, N_q, Hq, Hkv, 128)
+        p = la.lean_attn_problem_schedule(pr, seqlens, tn)
+        assert (p.C_m, p.T_m, p.kernel) == (C_m, T_m, kernel), (N_q, Hq, Hkv)
+        assert p.num_output_tiles == 3 * Hkv * C_m
+        assert p.total_iters == Hkv * C_m * sum(math.ceil(n / p.T_n) for n in seqlens)
+        assert C_m * T_m >= R > (C_m - 1) * T_m
+        ws = la.lean_attn_problem_workspace_size(pr)
+        assert ws >= 256 + 4 * 4096 + 4096 * T_m * (128 + 2) * 4 and ws % 256 == 0
+    # the plain decode entry points are the N_q = 1 problem
+    p1 = _plan(seqlens, 64, 2, 128, la.BF16, la.KV_PADDED, num_cus=256)
+    p2 = la.lean_attn_problem_schedule(_problem(3, 1, 64, 2, 128), seqlens, tn)
+    assert bytes(p1) == bytes(p2)
+    assert la.lean_attn_workspace_size(3, 64, 2, 128, la.BF16) == la.lean_attn_problem_workspace_size(_problem(3, 1, 64, 2, 128))
+
+
+@pytest.mark.parametrize("layout", [la.KV_PADDED, la.KV_PACKED])
+@pytest.mark.parametrize("G", [1, 7, 64, 300])
+def test_span_invariants_with_row_blocks(layout, G):
+    seqlens = [1024, 20000, 0, 77, 129]
+    pr = _problem(len(seqlens), 5, 28, 4, 128, layout=layout, causal=1)      # 35 rows per KV head: 3 blocks
+    p = la.lean_attn_problem_schedule(pr, seqlens, la.Tuning(num_cus=G, ctas_per_cu=1, grid=G))
+    assert p.C_m == 3
+    _check_invariants(seqlens, 4, layout, p)
+
+
+def test_problem_argument_errors():
+    tn = la.Tuning(num_cus=4)
+    def status(pr, seqlens):
+        with pytest.raises(la.LeanAttnError) as e:
+            la.lean_attn_problem_schedule(pr, seqlens, tn)
+        return e.value.status
+    assert status(_problem(1, 0, 2, 2, 128), [10]) == -2
+    assert status(_problem(1, 17, 32, 2, 128), [100]) == -2            # 272 query rows per KV head
+    assert status(_problem(1, 4, 2, 2, 128, causal=1), [3]) == -5      # fewer cached tokens than query rows
+    assert status(_problem(1, 4, 2, 2, 128, causal=2), [30]) == -2
+    assert status(_problem(1, 4, 2, 2, 128, out_dtype=7), [30]) == -3
+    la.lean_attn_problem_schedule(_problem(2, 4, 2, 2, 128, causal=1), [4, 0], tn)   # exactly N_q tokens, and empty
+    la.lean_attn_problem_schedule(_problem(1, 4, 2, 2, 128, causal=0), [3], tn)      # no mask: any length
+    with pytest.raises(la.LeanAttnError) as e:                                       # VALU kernel: one row per KV head
+        la.lean_attn_problem_schedule(_problem(1, 2, 2, 2, 128), [30], la.Tuning(num_cus=4, kernel=1))
+    assert e.value.status == -8
+    assert la.lean_attn_problem_workspace_size(_problem(1, 1, 2, 2, 96)) == 0
 
 
 def test_span_invariants_on_benchmark_shapes():
@@ -215,7 +275,7 @@ def test_argument_errors():
         _plan([1] * 257, 2, 2, 128, la.BF16, la.KV_PADDED, num_cus=4)
     assert e.value.status == -6
     with pytest.raises(la.LeanAttnError) as e:
-        _plan([10], 34, 2, 128, la.BF16, la.KV_PADDED, num_cus=4)       # group of 17
+        _plan([10], 514, 2, 128, la.BF16, la.KV_PADDED, num_cus=4)      # 257 query rows per KV head
     assert e.value.status == -2
     with pytest.raises(la.LeanAttnError) as e:
         _plan([10], 4, 2, 128, la.BF16, la.KV_PADDED, num_cus=4, kernel=1)  # VALU kernel needs Hq == Hkv

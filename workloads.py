@@ -34,6 +34,8 @@ class Workload:
     outlier_frac: float = 0.0       # fraction of key rows scaled by outlier_gain
     outlier_gain: float = 8.0
     note: str = ""
+    N_q: int = 1                    # query rows per sequence (the last N_q cached tokens)
+    causal: bool = False            # query row i sees the first N_b - N_q + i + 1 cached tokens
 
     @property
     def scale(self) -> float:
@@ -90,7 +92,7 @@ def scaled_down(w: Workload, factor: int, min_len: int = 1) -> Workload:
 @dataclass
 class Inputs:
     w: Workload
-    q: torch.Tensor                 # [B, Hq, D]
+    q: torch.Tensor                 # [B, Hq, D], or [B, N_q, Hq, D] when N_q > 1
     k: torch.Tensor                 # PADDED [B, Hkv, n_stride, D] | PACKED [Hkv, total, D]
     v: torch.Tensor
     seqlens: List[int] = field(default_factory=list)
@@ -109,7 +111,9 @@ def generate(w: Workload, device="cpu", slab_rows: int = 1 << 16) -> Inputs:
     gen = torch.Generator(device=dev)
     gen.manual_seed(1000 + w.seed)
     dt = w.torch_dtype
-    q = torch.randn(w.B, w.Hq, w.D, generator=gen, device=dev, dtype=torch.float32).to(dt)
+    q = torch.randn(w.B, w.N_q, w.Hq, w.D, generator=gen, device=dev, dtype=torch.float32).to(dt)
+    if w.N_q == 1:
+        q = q.view(w.B, w.Hq, w.D)
     if w.kv_layout == KV_PADDED:
         shape = (w.B * w.Hkv * w.n_stride, w.D)
         final = (w.B, w.Hkv, w.n_stride, w.D)
