@@ -65,7 +65,7 @@ typedef enum lean_attn_out_dtype { LEAN_ATTN_OUT_F32 = 0, LEAN_ATTN_OUT_AS_INPUT
 typedef enum lean_attn_kv_layout { LEAN_ATTN_KV_PADDED = 0, LEAN_ATTN_KV_PACKED = 1 } lean_attn_kv_layout;
 
 #define LEAN_ATTN_MAX_BATCH 256  /* sequences per call (the schedule table travels as kernel arguments) */
-#define LEAN_ATTN_MAX_TILE_ROWS 16    /* query rows of one output tile (rows of one MFMA tile) */
+#define LEAN_ATTN_MAX_TILE_ROWS 32    /* query rows of one output tile: two MFMA row blocks (one, 16 rows, at D = 256) */
 #define LEAN_ATTN_MAX_QUERY_ROWS 256  /* N_q * Hq / Hkv: query rows that share one KV head */
 #define LEAN_ATTN_MAX_GRID 4096  /* upper bound on workgroups; sizes the workspace */
 
@@ -73,11 +73,12 @@ typedef enum lean_attn_kv_layout { LEAN_ATTN_KV_PADDED = 0, LEAN_ATTN_KV_PACKED 
  * The stream-K schedule of one call (Section 4.3 and the first lines of
  * Algorithm 2).  The R = N_q * Hq / Hkv query rows that share a KV head (row =
  * query token * (Hq / Hkv) + head within the group) are cut into
- * C_m = ceil(R / 16) blocks of T_m = ceil(R / C_m) rows (the last may hold fewer).
+ * C_m = ceil(R / 32) blocks (ceil(R / 16) at D = 256) of T_m = ceil(R / C_m) rows
+ * (the last may hold fewer).
  * Output tile = one (sequence, KV head, row block); it owns ceil(N_b / T_n)
  * LeanTile iterations.  CTA g owns iterations
  * [g*iters_per_cta + min(g, extra), ... + iters_per_cta + (g < extra)).
- * For decode with up to 16 query heads per KV head, C_m = 1 and T_m = Hq / Hkv.
+ * For decode with up to 32 query heads per KV head, C_m = 1 and T_m = Hq / Hkv.
  */
 typedef struct lean_attn_plan {
     int32_t T_n;              /* LeanTile size in tokens */
@@ -129,8 +130,8 @@ typedef struct lean_attn_tuning {
  *   causal = 1: query row i attends to the first N_b - N_q + i + 1 cached rows
  *               (the decoder mask, aligned to the end of the context; the paper
  *               does not discuss masks).  Needs N_b >= N_q or N_b == 0.
- * Every block of up to 16 query rows streams the K/V of its head once: for
- * N_q * Hq / Hkv > 16 the K/V traffic grows by C_m.  This is a decode-phase
+ * Every output tile of up to 32 query rows (16 at D = 256) streams the K/V of its
+ * head once: beyond that the K/V traffic grows by C_m.  This is a decode-phase
  * path for short query tiles (speculative decoding, chunked prefill tails), not
  * a prefill kernel.  Limits: N_q * Hq / Hkv <= LEAN_ATTN_MAX_QUERY_ROWS.
  */

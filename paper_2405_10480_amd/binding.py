@@ -16,7 +16,7 @@ from . import buildlib as _build
 F16, BF16 = 0, 1
 KV_PADDED, KV_PACKED = 0, 1
 OUT_F32, OUT_AS_INPUT = 0, 1
-MAX_BATCH, MAX_TILE_ROWS, MAX_QUERY_ROWS, MAX_GRID = 256, 16, 256, 4096
+MAX_BATCH, MAX_TILE_ROWS, MAX_QUERY_ROWS, MAX_GRID = 256, 32, 256, 4096
 
 OK = 0
 ERR_NULL_POINTER, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE = -1, -2, -3, -4

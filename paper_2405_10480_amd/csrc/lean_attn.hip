@@ -58,6 +58,10 @@ static Variant mha_shape(int shape) {  // <loads per lane per stream, waves, dou
 
 template <int DT, int D>
 static Variant gqa_shape(int shape) {  // <16-token blocks per wave per step, waves, double-buffered>
+    // The default keeps 32 KiB or more in flight per compute unit with rows of any length:
+    // eight waves at D = 64 (4 KiB per wave and step), two blocks per wave at D = 256.
+    if (shape == 0 && D == 64) shape = 4;
+    if (shape == 0 && D == 256) shape = 5;
     switch (shape) {
         case 0: return variant_of<GqaCore<DT, D, 1, 4, false>>();
         case 1: return variant_of<GqaCore<DT, D, 2, 4, true>>();
@@ -68,12 +72,33 @@ static Variant gqa_shape(int shape) {  // <16-token blocks per wave per step, wa
     }
 }
 
+// Two blocks of 16 query rows per pass over K/V (17..32 rows per output tile, D <= 128).  Only the
+// single-buffered shapes are built: the second set of accumulators takes the registers of the
+// second load buffer.
+template <int DT, int D>
+static Variant gqa_shape_two_blocks(int shape) {
+    if (shape == 0) shape = D == 64 ? 4 : 5;  // measured best: eight waves at D = 64, two token blocks at D = 128
+    switch (shape) {
+        case 0: case 2: return variant_of<GqaCore<DT, D, 1, 4, false, 2>>();
+        case 3: case 4: return variant_of<GqaCore<DT, D, 1, 8, false, 2>>();
+        default: return variant_of<GqaCore<DT, D, 2, 4, false, 2>>();
+    }
+}
+
 static int dim_index(int D) { return D == 64 ? 0 : D == 128 ? 1 : D == 256 ? 2 : -1; }
 
-// kernel: 0 VALU single-row core, 1 MFMA query-group core
-static bool pick_variant(int kernel, int dtype, int D, int shape, Variant* v) {
-    if (shape < 0 || shape >= kNumShapes || dim_index(D) < 0) return false;
+// Most query rows one output tile can hold: two MFMA row blocks up to D = 128, one at D = 256.
+static int max_tile_rows(int D) { return D <= 128 ? LEAN_ATTN_MAX_TILE_ROWS : 16; }
+
+// kernel: 0 VALU single-row core, 1 MFMA query-group core; T_m: query rows per output tile
+static bool pick_variant(int kernel, int dtype, int D, int shape, int T_m, Variant* v) {
+    if (shape < 0 || shape >= kNumShapes || dim_index(D) < 0 || T_m < 1 || T_m > max_tile_rows(D)) return false;
     const bool bf = dtype == LEAN_ATTN_BF16;
+    if (kernel == 1 && T_m > 16) {
+        if (D == 64) *v = bf ? gqa_shape_two_blocks<kDtBF16, 64>(shape) : gqa_shape_two_blocks<kDtF16, 64>(shape);
+        else *v = bf ? gqa_shape_two_blocks<kDtBF16, 128>(shape) : gqa_shape_two_blocks<kDtF16, 128>(shape);
+        return true;
+    }
     if (kernel == 0) {
         if (D == 64) *v = bf ? mha_shape<kDtBF16, 64>(shape) : mha_shape<kDtF16, 64>(shape);
         else if (D == 128) *v = bf ? mha_shape<kDtBF16, 128>(shape) : mha_shape<kDtF16, 128>(shape);
@@ -89,12 +114,12 @@ static bool pick_variant(int kernel, int dtype, int D, int shape, Variant* v) {
 // Unit count of the device and, per variant, the workgroups that fit on one unit (cached).
 struct DeviceInfo {
     int cus = 0;
-    int resident[2][2][3][kNumShapes] = {};  // [kernel][dtype][head dim][shape], 0 = not yet queried
+    int resident[3][2][3][kNumShapes] = {};  // [VALU, MFMA, MFMA two row blocks][dtype][head dim][shape], 0 = not yet queried
 };
 static DeviceInfo g_dev[64];
 static std::mutex g_dev_mutex;
 
-static int query_device(int kernel, int dtype, int D, int shape, int* cus, int* per_cu) {
+static int query_device(int kernel, int dtype, int D, int shape, int T_m, int* cus, int* per_cu) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LEAN_ATTN_ERR_HIP;
     std::lock_guard<std::mutex> lock(g_dev_mutex);
@@ -105,10 +130,10 @@ static int query_device(int kernel, int dtype, int D, int shape, int* cus, int* 
         di.cus = prop.multiProcessorCount;
     }
     if (dim_index(D) < 0) return LEAN_ATTN_ERR_UNSUPPORTED;
-    int& n = di.resident[kernel][dtype][dim_index(D)][shape];
+    int& n = di.resident[kernel == 1 && T_m > 16 ? 2 : kernel][dtype][dim_index(D)][shape];
     if (n == 0) {
         Variant v;
-        if (!pick_variant(kernel, dtype, D, shape, &v)) return LEAN_ATTN_ERR_UNSUPPORTED;
+        if (!pick_variant(kernel, dtype, D, shape, T_m, &v)) return LEAN_ATTN_ERR_UNSUPPORTED;
         int blocks = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, v.fn, v.threads, 0) != hipSuccess || blocks <= 0)
             return LEAN_ATTN_ERR_HIP;
@@ -131,15 +156,17 @@ static int check_problem(const lean_attn_problem& p) {
     return LEAN_ATTN_OK;
 }
 
-// The R = N_q * group query rows that share a KV head, cut into C_m blocks of T_m <= 16 rows
-// (Algorithm 2: C_m = ceil(N_q / T_m), with the query group folded into the rows).
+// The R = N_q * group query rows that share a KV head, cut into C_m output tiles of T_m rows
+// (Algorithm 2: C_m = ceil(N_q / T_m), with the query group folded into the rows); a tile holds
+// at most 32 rows (16 at D = 256).
 struct RowBlocks {
     int R, C_m, T_m;
 };
 static RowBlocks row_blocks(const lean_attn_problem& p) {
     RowBlocks rb;
     rb.R = p.N_q * (p.Hq / p.Hkv);
-    rb.C_m = (rb.R + LEAN_ATTN_MAX_TILE_ROWS - 1) / LEAN_ATTN_MAX_TILE_ROWS;
+    const int cap = max_tile_rows(p.D);
+    rb.C_m = (rb.R + cap - 1) / cap;
     rb.T_m = (rb.R + rb.C_m - 1) / rb.C_m;
     return rb;
 }
@@ -189,7 +216,7 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
         kernel = 1;
     }
     Variant var;
-    if (!pick_variant(kernel, dtype, D, t.tile_shape, &var)) return LEAN_ATTN_ERR_UNSUPPORTED;
+    if (!pick_variant(kernel, dtype, D, t.tile_shape, T_m, &var)) return LEAN_ATTN_ERR_UNSUPPORTED;
     const int T_n = var.T_n;
 
     int64_t iters = 0, toks = 0;
@@ -215,7 +242,7 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
     int64_t resident;
     if (cus <= 0) {  // read the device: unit count and how many workgroups of this kernel fit per unit
         int hw_per_cu = 0;
-        rc = query_device(kernel, dtype, D, t.tile_shape, &cus, &hw_per_cu);
+        rc = query_device(kernel, dtype, D, t.tile_shape, T_m, &cus, &hw_per_cu);
         if (rc != LEAN_ATTN_OK) return rc;
         if (hw_per_cu <= 0) return LEAN_ATTN_ERR_HIP;
         if (per_cu <= 0) per_cu = hw_per_cu < kDefaultCtasPerCu ? hw_per_cu : kDefaultCtasPerCu;
@@ -413,7 +440,8 @@ int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void
     }
 
     Variant var;
-    if (!pick_variant(plan.kernel, p.dtype, D, tuning ? tuning->tile_shape : 0, &var)) return LEAN_ATTN_ERR_UNSUPPORTED;
+    if (!pick_variant(plan.kernel, p.dtype, D, tuning ? tuning->tile_shape : 0, plan.T_m, &var))
+        return LEAN_ATTN_ERR_UNSUPPORTED;
 
     const RowBlocks rb = row_blocks(p);
     a.q = (const uint16_t*)q;

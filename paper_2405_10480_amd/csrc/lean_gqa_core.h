@@ -79,18 +79,21 @@ struct Piece<2> {
     using type = u32x2;
 };
 
-template <int DT, int D, int NBLK, int NW, bool DB = true>
+// MB: blocks of 16 query rows that share one pass over K/V (T_m <= 16 * MB).  Every K and V
+// register tile feeds MB score and MB output contractions.
+template <int DT, int D, int NBLK, int NW, bool DB = true, int MB = 1>
 struct GqaCore {
     static constexpr int kD = D;
     static constexpr int kDT = DT;
     static constexpr int kTn = NW * NBLK * 16;  // LeanTile
     static constexpr int kCH = NBLK * 16;       // tokens per wave per step
     static constexpr int kThreads = NW * 64;
-    static constexpr int kTmMax = 16;
+    static constexpr int kTmMax = 16 * MB;
     static constexpr int kStreams = NW;
-    // at D = 256 a four-wave workgroup needs more than half of the register file per wave;
-    // it then runs as the only workgroup of its compute unit (the default launch shape anyway)
-    static constexpr int kMinWavesPerSimd = (D == 256 && NW == 4) ? 1 : 2;
+    // with 256 output columns per query row block set (D = 256, or two row blocks at D = 128) a
+    // four-wave workgroup needs more than half of the register file per wave; it then runs as
+    // the only workgroup of its compute unit (the default launch shape anyway)
+    static constexpr int kMinWavesPerSimd = (D * MB >= 256 && NW == 4) ? 1 : 2;
     static constexpr int kKC = D / 32;          // 16-byte K pieces per lane per block
     static constexpr int kEV = D / 16;          // head-dim elements per lane per token (V side)
     static constexpr int kVW = kEV / 2;         // dwords per lane per token (V side)
@@ -144,24 +147,29 @@ struct GqaCore {
 
         // Q^T as B operands: lane (row r, g) holds Q[r][32*c2 + 8*g .. +8), zero rows past the block.
         // n_vis: cached tokens the lane's query row may attend to (causal mask aligned to the end).
-        u32x4 qb[kKC];
+        u32x4 qb[MB][kKC];
+        int n_vis[MB];
+        float m_run[MB];  // row 16*mb + r, shared by the four k-group lanes
+        float l_run[MB];  // this lane's share of l (tokens 4*i + g); summed over g at the end
+        f32x4 acc[MB][kEV];
 #pragma unroll
-        for (int c2 = 0; c2 < kKC; ++c2) qb[c2] = u32x4{0u, 0u, 0u, 0u};
-        int n_vis = n_ctx;
-        if (r < tr.count) {
-            int token;
-            const int64_t qrow = query_row(a, sg.b, tr.hk, tr.rho0 + r, &token);
-            if (a.causal) n_vis = n_ctx - a.N_q + token + 1;
-            const u32x4* qp = reinterpret_cast<const u32x4*>(a.q + qrow * D) + g;
+        for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-            for (int c2 = 0; c2 < kKC; ++c2) qb[c2] = qp[4 * c2];
+            for (int c2 = 0; c2 < kKC; ++c2) qb[mb][c2] = u32x4{0u, 0u, 0u, 0u};
+            n_vis[mb] = n_ctx;
+            if (16 * mb + r < tr.count) {
+                int token;
+                const int64_t qrow = query_row(a, sg.b, tr.hk, tr.rho0 + 16 * mb + r, &token);
+                if (a.causal) n_vis[mb] = n_ctx - a.N_q + token + 1;
+                const u32x4* qp = reinterpret_cast<const u32x4*>(a.q + qrow * D) + g;
+#pragma unroll
+                for (int c2 = 0; c2 < kKC; ++c2) qb[mb][c2] = qp[4 * c2];
+            }
+            m_run[mb] = -INFINITY;
+            l_run[mb] = 0.f;
+#pragma unroll
+            for (int e = 0; e < kEV; ++e) acc[mb][e] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
-
-        float m_run = -INFINITY;  // head r, shared by the four k-group lanes
-        float l_run = 0.f;        // this lane's share of l (tokens 4*i + g); summed over g at the end
-        f32x4 acc[kEV];
-#pragma unroll
-        for (int e = 0; e < kEV; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
 
         vvec kA[NBLK][4], kB[NBLK][4];
         vvec vA[NBLK][4], vB[NBLK][4];
@@ -218,59 +226,64 @@ struct GqaCore {
                     kb[blk][c2] = *reinterpret_cast<const u32x4*>(stage + stage_rd + (uint32_t)(blk * 16) * kStageRow + c2 * 64u);
             }
             __builtin_amdgcn_wave_barrier();
-            f32x4 s[NBLK];
-            float mx = -INFINITY;
+            uint2 p_hi[MB][NBLK], p_lo[MB][NBLK];
 #pragma unroll
-            for (int blk = 0; blk < NBLK; ++blk) {
-                // two accumulators halve the dependent MFMA chain over the head dim
-                f32x4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
+            for (int mb = 0; mb < MB; ++mb) {
+                f32x4 s[NBLK];
+                float mx = -INFINITY;
 #pragma unroll
-                for (int c2 = 0; c2 < kKC; ++c2) {
-                    c0 = mfma16<DT>(make_uint2(kb[blk][c2].x, kb[blk][c2].y), make_uint2(qb[c2].x, qb[c2].y), c0);
-                    c1 = mfma16<DT>(make_uint2(kb[blk][c2].z, kb[blk][c2].w), make_uint2(qb[c2].z, qb[c2].w), c1);
+                for (int blk = 0; blk < NBLK; ++blk) {
+                    // two accumulators halve the dependent MFMA chain over the head dim
+                    f32x4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int c2 = 0; c2 < kKC; ++c2) {
+                        c0 = mfma16<DT>(make_uint2(kb[blk][c2].x, kb[blk][c2].y),
+                                        make_uint2(qb[mb][c2].x, qb[mb][c2].y), c0);
+                        c1 = mfma16<DT>(make_uint2(kb[blk][c2].z, kb[blk][c2].w),
+                                        make_uint2(qb[mb][c2].z, qb[mb][c2].w), c1);
+                    }
+                    f32x4 c = c0 + c1;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float x = c[i] * a.scale_log2e;
+                        if (base + blk * 16 + 4 * i + g >= n_vis[mb]) x = -INFINITY;  // tail and masked tokens
+                        c[i] = x;
+                        mx = fmaxf(mx, x);
+                    }
+                    s[blk] = c;
                 }
-                f32x4 c = c0 + c1;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    float x = c[i] * a.scale_log2e;
-                    if (base + blk * 16 + 4 * i + g >= n_vis) x = -INFINITY;  // tail and masked tokens
-                    c[i] = x;
-                    mx = fmaxf(mx, x);
+                // The reference maximum m_run of a row is shared by its four k-group lanes.  It is
+                // only raised when some score of the wave exceeds it by more than kSlack (base-2
+                // units): any reference gives the same O~/l, so between updates P may reach 2^kSlack
+                // and the cross-lane maximum and the re-scaling of O stay off the common path.
+                constexpr float kSlack = 8.f;
+                float alpha = 1.f;
+                if (__any(mx > m_run[mb] + kSlack)) {
+                    mx = fmaxf(mx, xor_shuffle(mx, 16));
+                    mx = fmaxf(mx, xor_shuffle(mx, 32));
+                    const float m_new = fmaxf(m_run[mb], mx);
+                    const float m_new_ref = m_new == -INFINITY ? 0.f : m_new;
+                    alpha = fast_exp2(m_run[mb] - m_new_ref);
+                    m_run[mb] = m_new;
                 }
-                s[blk] = c;
-            }
-            // The reference maximum m_run of a head is shared by its four k-group lanes.  It is
-            // only raised when some score of the wave exceeds it by more than kSlack (base-2
-            // units): any reference gives the same O~/l, so between updates P may reach 2^kSlack
-            // and the cross-lane maximum and the re-scaling of O stay off the common path.
-            constexpr float kSlack = 8.f;
-            float alpha = 1.f;
-            if (__any(mx > m_run + kSlack)) {
-                mx = fmaxf(mx, xor_shuffle(mx, 16));
-                mx = fmaxf(mx, xor_shuffle(mx, 32));
-                const float m_new = fmaxf(m_run, mx);
-                const float m_new_ref = m_new == -INFINITY ? 0.f : m_new;
-                alpha = fast_exp2(m_run - m_new_ref);
-                m_run = m_new;
-            }
-            const float m_ref = m_run == -INFINITY ? 0.f : m_run;
-            float psum = 0.f;
-            uint2 p_hi[NBLK], p_lo[NBLK];
+                const float m_ref = m_run[mb] == -INFINITY ? 0.f : m_run[mb];
+                float psum = 0.f;
 #pragma unroll
-            for (int blk = 0; blk < NBLK; ++blk) {
-                float p[4];
+                for (int blk = 0; blk < NBLK; ++blk) {
+                    float p[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    p[i] = fast_exp2(s[blk][i] - m_ref);
-                    psum += p[i];
+                    for (int i = 0; i < 4; ++i) {
+                        p[i] = fast_exp2(s[blk][i] - m_ref);
+                        psum += p[i];
+                    }
+                    split_pair<DT>(p[0], p[1], p_hi[mb][blk].x, p_lo[mb][blk].x);
+                    split_pair<DT>(p[2], p[3], p_hi[mb][blk].y, p_lo[mb][blk].y);
                 }
-                split_pair<DT>(p[0], p[1], p_hi[blk].x, p_lo[blk].x);
-                split_pair<DT>(p[2], p[3], p_hi[blk].y, p_lo[blk].y);
-            }
-            l_run = l_run * alpha + psum;
-            if (__any(alpha != 1.f)) {  // the running max moved for some head of this wave
+                l_run[mb] = l_run[mb] * alpha + psum;
+                if (__any(alpha != 1.f)) {  // the running max moved for some row of this wave
 #pragma unroll
-                for (int e = 0; e < kEV; ++e) acc[e] *= alpha;
+                    for (int e = 0; e < kEV; ++e) acc[mb][e] *= alpha;
+                }
             }
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk) {
@@ -280,8 +293,11 @@ struct GqaCore {
                     uint2 va;
                     va.x = __builtin_amdgcn_perm(vb[blk][1].dword(e >> 1), vb[blk][0].dword(e >> 1), sel);
                     va.y = __builtin_amdgcn_perm(vb[blk][3].dword(e >> 1), vb[blk][2].dword(e >> 1), sel);
-                    acc[e] = mfma16<DT>(va, p_hi[blk], acc[e]);
-                    acc[e] = mfma16<DT>(va, p_lo[blk], acc[e]);
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        acc[mb][e] = mfma16<DT>(va, p_hi[mb][blk], acc[mb][e]);
+                        acc[mb][e] = mfma16<DT>(va, p_lo[mb][blk], acc[mb][e]);
+                    }
                 }
             }
         };
@@ -316,21 +332,24 @@ struct GqaCore {
             }
         }
 
-        // l over the four k-group lanes of each head; m is already common to them.
-        l_run += xor_shuffle(l_run, 16);
-        l_run += xor_shuffle(l_run, 32);
-        // 16-byte stores; rows are padded by 4 floats so that the 16 heads hit different banks
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int mb = 0; mb < MB; ++mb) {
+            // l over the four k-group lanes of each row; m is already common to them.
+            l_run[mb] += xor_shuffle(l_run[mb], 16);
+            l_run[mb] += xor_shuffle(l_run[mb], 32);
+            // 16-byte stores; rows are padded by 4 floats so that the 16 rows hit different banks
 #pragma unroll
-            for (int e4 = 0; e4 < kEV; e4 += 4) {
-                const f32x4 v = {acc[e4][i], acc[e4 + 1][i], acc[e4 + 2][i], acc[e4 + 3][i]};
-                *reinterpret_cast<f32x4*>(&sm.area[w].o[r][col_of(4 * g + i, e4)]) = v;
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int e4 = 0; e4 < kEV; e4 += 4) {
+                    const f32x4 v = {acc[mb][e4][i], acc[mb][e4 + 1][i], acc[mb][e4 + 2][i], acc[mb][e4 + 3][i]};
+                    *reinterpret_cast<f32x4*>(&sm.area[w].o[16 * mb + r][col_of(4 * g + i, e4)]) = v;
+                }
             }
-        }
-        if (g == 0) {
-            sm.m[w][r] = m_run;
-            sm.l[w][r] = l_run;
+            if (g == 0) {
+                sm.m[w][16 * mb + r] = m_run[mb];
+                sm.l[w][16 * mb + r] = l_run[mb];
+            }
         }
         __syncthreads();
     }

@@ -30,28 +30,29 @@ __device__ __forceinline__ void merge_children(const DecodeArgs& a, OwnPartial<C
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
         const int c = tid + i * THREADS;
-        if (c >= n_chunks) break;
-        const int row = (4 * c) / D;
-        f32x4 oc[F - 1];
-        float mc[F - 1], lc[F - 1];
+        if (c < n_chunks) {  // (no early exit: the loop must unroll so that `own` stays in registers)
+            const int row = (4 * c) / D;
+            f32x4 oc[F - 1];
+            float mc[F - 1], lc[F - 1];
 #pragma unroll
-        for (int j = 0; j < F - 1; ++j) {
-            const int jj = j < nchild ? j : nchild - 1;  // past the last child: re-read it, weight it zero
-            const uint32_t slot = (uint32_t)(first + jj * step) * (uint32_t)a.slot * 4u;
-            oc[j] = partial_load16(ws, slot + 16u * c);
-            mc[j] = partial_load4(ws, slot + 4u * (n_elem + row));
-            lc[j] = partial_load4(ws, slot + 4u * (n_elem + T_m + row));
-        }
+            for (int j = 0; j < F - 1; ++j) {
+                const int jj = j < nchild ? j : nchild - 1;  // past the last child: re-read it, weight it zero
+                const uint32_t slot = (uint32_t)(first + jj * step) * (uint32_t)a.slot * 4u;
+                oc[j] = partial_load16(ws, slot + 16u * c);
+                mc[j] = partial_load4(ws, slot + 4u * (n_elem + row));
+                lc[j] = partial_load4(ws, slot + 4u * (n_elem + T_m + row));
+            }
 #pragma unroll
-        for (int j = 0; j < F - 1; ++j) {
-            const float m_cta = j < nchild ? mc[j] : -INFINITY;
-            const float m_new = fmaxf(m_cta, own.m[i]);
-            const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-            const float w_cta = fast_exp2(m_cta - m_ref);
-            const float w_own = fast_exp2(own.m[i] - m_ref);
-            own.l[i] = w_cta * lc[j] + w_own * own.l[i];
-            own.o[i] = w_cta * oc[j] + w_own * own.o[i];
-            own.m[i] = m_new;
+            for (int j = 0; j < F - 1; ++j) {
+                const float m_cta = j < nchild ? mc[j] : -INFINITY;
+                const float m_new = fmaxf(m_cta, own.m[i]);
+                const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+                const float w_cta = fast_exp2(m_cta - m_ref);
+                const float w_own = fast_exp2(own.m[i] - m_ref);
+                own.l[i] = w_cta * lc[j] + w_own * own.l[i];
+                own.o[i] = w_cta * oc[j] + w_own * own.o[i];
+                own.m[i] = m_new;
+            }
         }
     }
 }

@@ -59,11 +59,11 @@ def test_grid_is_units_times_residency_and_spans_are_equal():
     p = _plan([65536], 32, 32, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2, grid_multiple=4)
     assert p.grid == 2048
     # head dim 256: 1 KiB per wave-wide load is two rows, so the default LeanTile is 32 tokens
-    # for single query rows and 64 for query groups
+    # for single query rows; query groups take two 16-token blocks per wave: 128 tokens
     p = _plan([8192], 8, 8, 256, la.BF16, la.KV_PADDED, num_cus=256)
     assert (p.T_n, p.total_iters, p.grid) == (32, 8 * 256, 256)
     p = _plan([8192], 16, 2, 256, la.F16, la.KV_PADDED, num_cus=256)
-    assert (p.T_n, p.T_m, p.kernel, p.total_iters) == (64, 8, 1, 2 * 128)
+    assert (p.T_n, p.T_m, p.kernel, p.total_iters) == (128, 8, 1, 2 * 64)
     # query groups use the MFMA kernel, one output tile per KV head
     p = _plan([262144], 64, 8, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=2)
     assert p.kernel == 1 and p.T_m == 8 and p.num_output_tiles == 8
@@ -150,20 +150,23 @@ def _problem(B, N_q, Hq, Hkv, D, dtype=la.BF16, layout=la.KV_PADDED, causal=0, o
 def test_query_rows_are_cut_into_row_blocks():
     # Algorithm 2: C_m output tiles along the query dimension; the query group is folded into the rows
     tn = la.Tuning(num_cus=256)
-    cases = [  # N_q, Hq, Hkv -> R, C_m, T_m, kernel
-        (1, 8, 8, 1, 1, 1, 0), (1, 64, 8, 8, 1, 8, 1), (1, 64, 2, 32, 2, 16, 1), (1, 34, 2, 17, 2, 9, 1),
-        (4, 8, 8, 4, 1, 4, 1), (3, 16, 2, 24, 2, 12, 1), (16, 32, 2, 256, 16, 16, 1), (5, 28, 4, 35, 3, 12, 1),
+    cases = [  # D, N_q, Hq, Hkv -> R, C_m, T_m, kernel      (a tile holds up to 32 rows, 16 at D = 256)
+        (128, 1, 8, 8, 1, 1, 1, 0), (128, 1, 64, 8, 8, 1, 8, 1), (128, 1, 64, 2, 32, 1, 32, 1),
+        (128, 1, 34, 2, 17, 1, 17, 1), (64, 4, 8, 8, 4, 1, 4, 1), (64, 3, 16, 2, 24, 1, 24, 1),
+        (128, 16, 32, 2, 256, 8, 32, 1), (128, 5, 28, 4, 35, 2, 18, 1),
+        (256, 1, 64, 2, 32, 2, 16, 1), (256, 1, 34, 2, 17, 2, 9, 1), (256, 5, 28, 4, 35, 3, 12, 1),
+        (256, 16, 32, 2, 256, 16, 16, 1),
     ]
     seqlens = [5000, 0, 777]
-    for N_q, Hq, Hkv, R, C_m, T_m, kernel in cases:
-        pr = _problem(3, N_q, Hq, Hkv, 128)
+    for D, N_q, Hq, Hkv, R, C_m, T_m, kernel in cases:
+        pr = _problem(3, N_q, Hq, Hkv, D)
         p = la.lean_attn_problem_schedule(pr, seqlens, tn)
         assert (p.C_m, p.T_m, p.kernel) == (C_m, T_m, kernel), (N_q, Hq, Hkv)
         assert p.num_output_tiles == 3 * Hkv * C_m
         assert p.total_iters == Hkv * C_m * sum(math.ceil(n / p.T_n) for n in seqlens)
         assert C_m * T_m >= R > (C_m - 1) * T_m
         ws = la.lean_attn_problem_workspace_size(pr)
-        assert ws >= 256 + 4 * 4096 + 4096 * T_m * (128 + 2) * 4 and ws % 256 == 0
+        assert ws >= 256 + 4 * 4096 + 4096 * T_m * (D + 2) * 4 and ws % 256 == 0
     # the plain decode entry points are the N_q = 1 problem
     p1 = _plan(seqlens, 64, 2, 128, la.BF16, la.KV_PADDED, num_cus=256)
     p2 = la.lean_attn_problem_schedule(_problem(3, 1, 64, 2, 128), seqlens, tn)
@@ -175,7 +178,7 @@ def test_query_rows_are_cut_into_row_blocks():
 @pytest.mark.parametrize("G", [1, 7, 64, 300])
 def test_span_invariants_with_row_blocks(layout, G):
     seqlens = [1024, 20000, 0, 77, 129]
-    pr = _problem(len(seqlens), 5, 28, 4, 128, layout=layout, causal=1)      # 35 rows per KV head: 3 blocks
+    pr = _problem(len(seqlens), 5, 28, 4, 256, layout=layout, causal=1)      # 35 rows per KV head: 3 blocks
     p = la.lean_attn_problem_schedule(pr, seqlens, la.Tuning(num_cus=G, ctas_per_cu=1, grid=G))
     assert p.C_m == 3
     _check_invariants(seqlens, 4, layout, p)
