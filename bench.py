@@ -49,7 +49,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", type=int, default=2, help="named configuration 1..5")
+    ap.add_argument("--workload", type=int, default=2, help="named configuration 1..5 (6..8: widened shapes)")
     ap.add_argument("--ctas-per-cu", type=int, default=0)
     ap.add_argument("--grid", type=int, default=0)
     ap.add_argument("--xcd-remap", type=int, default=0)
@@ -88,16 +88,23 @@ def main() -> int:
     for _ in range(copies - 1):
         ks.append(inp.k.clone())
         vs.append(inp.v.clone())
-    ws = torch.empty(la.lean_attn_workspace_size(w.B, w.Hq, w.Hkv, w.D, code), dtype=torch.uint8, device=dev)
+    problem = la.Problem(B=w.B, N_q=w.N_q, Hq=w.Hq, Hkv=w.Hkv, D=w.D, dtype=code, out_dtype=la.OUT_F32,
+                         kv_layout=w.kv_layout, causal=int(w.causal), scale=w.scale, kv_seq_stride=w.n_stride)
+    ws = torch.empty(la.lean_attn_problem_workspace_size(problem), dtype=torch.uint8, device=dev)
     la.lean_attn_workspace_init(ws)
-    out = torch.empty(w.B, w.Hq, w.D, dtype=torch.float32, device=dev)
+    out = torch.empty(w.B, w.N_q, w.Hq, w.D, dtype=torch.float32, device=dev)
     tuning = la.Tuning(grid=args.grid, ctas_per_cu=args.ctas_per_cu, xcd_remap=args.xcd_remap)
-    plan = la.lean_attn_schedule(list(w.seqlens), w.Hq, w.Hkv, w.D, code, w.kv_layout, tuning)
+    plan = la.lean_attn_problem_schedule(problem, list(w.seqlens), tuning)
+
+    def launch(j: int, tn) -> None:
+        if w.N_q == 1:  # the decode entry point (the same kernels as the general one)
+            la.lean_attn_decode(inp.q, ks[j], vs[j], inp.seqlens, out.view(w.B, w.Hq, w.D), ws, Hkv=w.Hkv,
+                                kv_layout=w.kv_layout, kv_seq_stride=w.n_stride, scale=w.scale, tuning=tn)
+        else:
+            la.lean_attn_attend(problem, inp.q, ks[j], vs[j], inp.seqlens, out, ws, tuning=tn)
 
     def step(i: int) -> None:
-        j = i % copies
-        la.lean_attn_decode(inp.q, ks[j], vs[j], inp.seqlens, out, ws, Hkv=w.Hkv, kv_layout=w.kv_layout,
-                            kv_seq_stride=w.n_stride, scale=w.scale, tuning=tuning)
+        launch(i % copies, tuning)
 
     for i in range(args.warmup):
         step(i)
@@ -128,6 +135,26 @@ def main() -> int:
     torch.cuda.synchronize()
     amortised_ms = (time.perf_counter() - t1) * 1e3 / args.steps
 
+    # The same launches captured once in a HIP graph and replayed: the launch path leaves the
+    # host, what remains is the GPU-side cost per step (how a serving loop would issue it).
+    n_graph = min(args.steps, 100)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in range(n_graph):
+            step(i)
+    for _ in range(2):
+        graph.replay()
+    torch.cuda.synchronize()
+    ga, gb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    replays = max(1, args.steps // n_graph)
+    ga.record()
+    for _ in range(replays):
+        graph.replay()
+    gb.record()
+    torch.cuda.synchronize()
+    graph_ms = ga.elapsed_time(gb) / (replays * n_graph)
+    assert la.lean_attn_workspace_status(ws) == 0, "a host workgroup timed out waiting for a peer (graph replay)"
+
     # Streaming-read ceiling of this machine (context only): the same contiguous-share pattern
     # without arithmetic, with non-temporal loads (what the decode kernels use) and with default loads.
     sink = torch.zeros(64, dtype=torch.int32, device=dev)
@@ -153,21 +180,19 @@ def main() -> int:
     def timed_schedule(fixed_split: int, reps: int = 30) -> float:
         tn = la.Tuning(fixed_split=fixed_split)
         for i in range(3):
-            la.lean_attn_decode(inp.q, ks[i % copies], vs[i % copies], inp.seqlens, out, ws, Hkv=w.Hkv,
-                                kv_layout=w.kv_layout, kv_seq_stride=w.n_stride, scale=w.scale, tuning=tn)
+            launch(i % copies, tn)
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for i in range(reps):
-            la.lean_attn_decode(inp.q, ks[i % copies], vs[i % copies], inp.seqlens, out, ws, Hkv=w.Hkv,
-                                kv_layout=w.kv_layout, kv_seq_stride=w.n_stride, scale=w.scale, tuning=tn)
+            launch(i % copies, tn)
         b.record()
         torch.cuda.synchronize()
         return a.elapsed_time(b) / reps
 
     schedules = None
     if not args.no_schedule_comparison:
-        fs_plan = la.lean_attn_schedule(list(w.seqlens), w.Hq, w.Hkv, w.D, code, w.kv_layout, la.Tuning(fixed_split=-1))
+        fs_plan = la.lean_attn_problem_schedule(problem, list(w.seqlens), la.Tuning(fixed_split=-1))
         fs_ms, ns_ms = timed_schedule(-1), timed_schedule(1)
         schedules = {"stream_k_ms": round(amortised_ms, 5), "fixed_split_ms": round(fs_ms, 5),
                      "fixed_split_factor": int(fs_plan.fixed_split), "no_split_ms": round(ns_ms, 5),
@@ -196,6 +221,7 @@ def main() -> int:
         "latency_us": {"avg": round(avg_ms * 1e3, 2), "median": round(med_ms * 1e3, 2),
                        "p10": round(p10_ms * 1e3, 2), "p90": round(p90_ms * 1e3, 2)},
         "back_to_back_ms_per_step": round(amortised_ms, 5),
+        "graph_replay_ms_per_step": round(graph_ms, 5),
         "pct_of_hbm_peak": round(100.0 * gbps_kernel / HBM_PEAK_GBPS, 2),
         "higher_is_better": True,
         "scaling": "weak",
@@ -203,7 +229,8 @@ def main() -> int:
         "dtype": w.dtype,            # element type of Q/K/V; products and sums accumulate in f32
         "accumulate": "f32",
         "data": "synthetic",
-        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
+        "config": {"workload": w.name, "B": w.B, "N_q": w.N_q, "causal": bool(w.causal), "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
+                   "query_rows_per_tile": int(plan.T_m), "tiles_per_kv_head": int(plan.C_m),
                    "total_context": w.total_tokens, "kv_bytes": one_copy, "kv_layout": "packed" if w.kv_layout else "padded",
                    "grid": int(plan.grid), "lean_tile": int(plan.T_n), "iters": int(plan.total_iters),
                    "kernel": "mfma_group" if plan.kernel else "valu_row", "cache_copies_rotated": copies},
@@ -227,11 +254,11 @@ def main() -> int:
                 k_s, v_s = inp.k[:, :hs].contiguous().cpu(), inp.v[:, :hs].contiguous().cpu()
             else:
                 k_s, v_s = inp.k[:hs].contiguous().cpu(), inp.v[:hs].contiguous().cpu()
-            q_s = inp.q[:, :hs * group].contiguous().cpu()
+            q_s = inp.q.view(w.B, w.N_q, w.Hq, w.D)[:, :, :hs * group].contiguous().cpu()
             t = time.perf_counter()
-            _o, _l, threads = oracle.decode_attention(q_s, k_s, v_s, inp.seqlens, Hq=hs * group, Hkv=hs, D=w.D,
-                                                      scale=w.scale, kv_layout=w.kv_layout, n_stride=w.n_stride,
-                                                      return_threads=True)
+            _o, _l, threads = oracle.attention(q_s, k_s, v_s, inp.seqlens, N_q=w.N_q, Hq=hs * group, Hkv=hs, D=w.D,
+                                               scale=w.scale, causal=w.causal, kv_layout=w.kv_layout,
+                                               n_stride=w.n_stride, return_threads=True)
             return time.perf_counter() - t, threads
 
         t1, threads = sample(1)

@@ -311,6 +311,17 @@ def test_named_workloads_full_size(idx):
     print(f"{w.name}: max_abs={max_abs:.2e} rel_l2={rel_l2:.2e}")
 
 
+@pytest.mark.parametrize("idx", [6, 7, 8])
+def test_widened_named_workloads_full_size(idx):
+    # head dim 256; a causal query tile of 4 tokens x 4 heads per KV head; 32 query heads per KV head
+    w = workloads.named(idx)
+    inp = workloads.generate(w, device="cuda")
+    got, got_lse = _run_attend(inp)
+    want, want_lse = _oracle_attend(inp)
+    max_abs, rel_l2 = _check(got.cpu().numpy().reshape(want.shape), got_lse, want, want_lse, w.name)
+    print(f"{w.name}: max_abs={max_abs:.2e} rel_l2={rel_l2:.2e}")
+
+
 def test_ragged_batch_full_size_sampled_heads():
     # 17 GB of cache: the oracle checks every sequence for a seeded sample of KV heads
     w = workloads.named(4)

@@ -65,7 +65,7 @@ def _ragged_lengths(seed: int, B: int, lo: int, hi: int) -> tuple:
 
 
 def named(idx: int) -> Workload:
-    """The five benchmark configurations (index 1..5)."""
+    """The five benchmark configurations (index 1..5) and three widened shapes (6..8)."""
     if idx == 1:
         return Workload("cfg1_mha_b1_h8_d64_n4096_f16", 1, 8, 8, 64, "f16", (4096,), KV_PADDED, seed=1)
     if idx == 2:
@@ -80,7 +80,18 @@ def named(idx: int) -> Workload:
     if idx == 5:
         return Workload("cfg5_gqa_b4_h56_kv8_d128_outliers_bf16", 4, 56, 8, 128, "bf16",
                         (3000, 17000, 100003, 250001), KV_PACKED, seed=5, outlier_frac=0.01)
-    raise ValueError("workload index must be 1..5")
+    # Widened rows of the same path (not among the five headline configurations): head dim 256,
+    # a causal query tile of 4 tokens per sequence (speculative decoding), 32 query heads per KV head.
+    if idx == 6:
+        return Workload("cfg6_gqa_b4_h32_kv4_d256_n65536_bf16", 4, 32, 4, 256, "bf16", (65536,) * 4, KV_PADDED,
+                        seed=6)
+    if idx == 7:
+        return Workload("cfg7_gqa_b4_h32_kv8_d128_n65536_q4_causal_bf16", 4, 32, 8, 128, "bf16", (65536,) * 4,
+                        KV_PADDED, seed=7, N_q=4, causal=True)
+    if idx == 8:
+        return Workload("cfg8_mqa_b4_h64_kv2_d128_n262144_bf16", 4, 64, 2, 128, "bf16", (262144,) * 4, KV_PADDED,
+                        seed=8)
+    raise ValueError("workload index must be 1..8")
 
 
 def scaled_down(w: Workload, factor: int, min_len: int = 1) -> Workload:
