@@ -74,6 +74,7 @@ def main() -> int:
         return 3
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    props = torch.cuda.get_device_properties(0)
     w = workloads.named(args.workload)
     code = la.F16 if w.dtype == "f16" else la.BF16
 
@@ -134,6 +135,24 @@ def main() -> int:
         step(i)
     torch.cuda.synchronize()
     amortised_ms = (time.perf_counter() - t1) * 1e3 / args.steps
+
+    # Warm cache, for problems that fit the last-level cache (labelled as such, never the headline):
+    # the same K/V copy every step.
+    warm_us = None
+    if one_copy <= LLC_BYTES // 2:
+        for _ in range(10):
+            launch(0, tuning)
+        torch.cuda.synchronize()
+        n_warm = min(args.steps, 100)
+        wa = [torch.cuda.Event(enable_timing=True) for _ in range(n_warm)]
+        wb = [torch.cuda.Event(enable_timing=True) for _ in range(n_warm)]
+        for i in range(n_warm):   # timed exactly like the cold loop above
+            wa[i].record()
+            launch(0, tuning)
+            wb[i].record()
+        torch.cuda.synchronize()
+        lat = [a.elapsed_time(b) for a, b in zip(wa, wb)]
+        warm_us = round(sorted(lat)[len(lat) // 2] * 1e3, 2)
 
     # The same launches captured once in a HIP graph and replayed: the launch path leaves the
     # host, what remains is the GPU-side cost per step (how a serving loop would issue it).
@@ -222,6 +241,7 @@ def main() -> int:
                        "p10": round(p10_ms * 1e3, 2), "p90": round(p90_ms * 1e3, 2)},
         "back_to_back_ms_per_step": round(amortised_ms, 5),
         "graph_replay_ms_per_step": round(graph_ms, 5),
+        "warm_cache_latency_us_median": warm_us,   # null unless the KV cache fits the last-level cache
         "pct_of_hbm_peak": round(100.0 * gbps_kernel / HBM_PEAK_GBPS, 2),
         "higher_is_better": True,
         "scaling": "weak",
@@ -231,11 +251,13 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "N_q": w.N_q, "causal": bool(w.causal), "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
                    "query_rows_per_tile": int(plan.T_m), "tiles_per_kv_head": int(plan.C_m),
-                   "total_context": w.total_tokens, "kv_bytes": one_copy, "kv_layout": "packed" if w.kv_layout else "padded",
+                   "seqlens": list(w.seqlens) if w.B <= 32 else None, "total_context": w.total_tokens, "kv_bytes": one_copy, "kv_layout": "packed" if w.kv_layout else "padded",
                    "grid": int(plan.grid), "lean_tile": int(plan.T_n), "iters": int(plan.total_iters),
                    "kernel": "mfma_group" if plan.kernel else "valu_row", "cache_copies_rotated": copies},
         "roofline": {"bound": "hbm", "achieved": round(gbps_kernel, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gbps_kernel / HBM_PEAK_GBPS, 4), "traffic": _traffic_from_profiles(w.name)},
+        "device": {"name": props.name, "compute_units": props.multi_processor_count,
+                   "hbm_bytes": props.total_memory},
         "stream_read_probe_GBps": {"non_temporal_loads": round(probe_nt_gbps, 1), "default_loads": round(probe_gbps, 1)},
         "schedule_comparison": schedules,
         "paper_context": "LeanAttention reports speedups over FlashDecoding only (avg 1.73x, up to 2.18x at 256k, "

@@ -79,7 +79,9 @@ template <int DT, int D>
 static Variant gqa_shape_two_blocks(int shape) {
     if (shape == 0) shape = D == 64 ? 4 : 5;  // measured best: eight waves at D = 64, two token blocks at D = 128
     switch (shape) {
-        case 0: case 2: return variant_of<GqaCore<DT, D, 1, 4, false, 2>>();
+        case 0: return variant_of<GqaCore<DT, D, 1, 4, false, 2>>();
+        case 1: return variant_of<GqaCore<DT, D, 2, 4, true, 2>>();
+        case 2: return variant_of<GqaCore<DT, D, 1, 4, true, 2>>();
         case 3: case 4: return variant_of<GqaCore<DT, D, 1, 8, false, 2>>();
         default: return variant_of<GqaCore<DT, D, 2, 4, false, 2>>();
     }

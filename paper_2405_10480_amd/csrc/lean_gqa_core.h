@@ -1,17 +1,17 @@
-// LeanTile inner loop (Algorithm 1) for a group of T_m <= 16 query heads that
-// share one KV head.  The group forms the T_m rows of Q_f, so each K/V tile is
-// read once for the whole group and QK^T / PV are small dense contractions:
-// they run on the matrix cores (v_mfma_f32_16x16x16 in bf16 or f16), with the
-// online softmax in fp32 on the VALU.
+// LeanTile inner loop (Algorithm 1) for T_m <= 16 * MB query rows that share one KV
+// head (a group of query heads, several query tokens, or both).  The rows are the T_m
+// rows of Q_f, so each K/V tile is read once for all of them and QK^T / PV are small
+// dense contractions: they run on the matrix cores (v_mfma_f32_16x16x32 in bf16 or
+// f16), with the online softmax in fp32 on the VALU.
 //
 // Per wave and per block of 16 tokens (indices below are within the block):
 //
-//   S^T[16 tok x 16 head] = K_blk * Q^T         A = K (m: token, k: head dim), B = Q^T
+//   S^T[16 tok x 16 rows] = K_blk * Q^T         A = K (m: token, k: head dim), B = Q^T
 //     lane (r = lane%16, g = lane/16) supplies token 4*(r%4) + r/4, so that the
-//     accumulator register i of lane (h, g) is the score of token 4*i + g for
-//     head h: exactly the B-operand layout (k = 4*g + j <-> token 4*j + g) of
+//     accumulator register i of lane (h, g) is the score of token 4*i + g for query
+//     row h: the tokens a lane group needs as contraction slots of
 //
-//   O^T[D x 16 head] += V_blk^T * P^T            A = V^T (m: head dim, k: token), B = P^T
+//   O^T[D x 16 rows] += V_blk^T * P^T            A = V^T (m: head dim, k: token), B = P^T
 //     lane (m = lane%16, g) loads, for j = 0..3, the D/16 head-dim elements
 //     [m*D/16, (m+1)*D/16) of token 4*j + g: the four loads of a wave are fully
 //     coalesced (one contiguous KiB each at D = 128), and the 4-token x D/16
@@ -20,8 +20,10 @@
 //     O[h][ (D/16)*(4*g + i) + e ].  (At D = 256 the 16 elements of a lane are two runs
 //     of 8, half a row apart, so that every load instruction stays contiguous.)
 //
-// P is split into a high and a low 16-bit part (P = P_hi + P_lo, two MFMAs per
-// operand) so that rounding P to the input precision never limits accuracy.
+// P is split into a high and a low 16-bit part (P = P_hi + P_lo) so that rounding P to the
+// input precision never limits accuracy.  The two parts share one MFMA: its 32 contraction
+// slots hold the 16 tokens twice, once against P_hi and once against P_lo.  For S^T the 32
+// slots are 32 consecutive head-dim elements.
 //
 // K is loaded with the same fully coalesced pattern as V (whole rows per group of 16
 // lanes).  The A operand of S^T needs a different lane<->row assignment (lane r holds
@@ -36,14 +38,19 @@
 
 namespace lean {
 
+// D[16x16] += A[16x32] * B[32x16] on the matrix cores (v_mfma_f32_16x16x32_bf16 / _f16 of
+// gfx950).  Lane (r = lane%16, g = lane/16) supplies row r of A and column r of B for the 8
+// contraction slots of its lane group, in its four operand dwords (two 16-bit elements each);
+// the product pairs slot (g, j) of A with slot (g, j) of B.  Accumulator register i of lane
+// (r, g) is D[4*g + i][r].
 template <int DT>
-__device__ __forceinline__ f32x4 mfma16(uint2 a, uint2 b, f32x4 c) {
+__device__ __forceinline__ f32x4 mfma32(u32x4 a, u32x4 b, f32x4 c) {
     if constexpr (DT == kDtBF16) {
-        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a), __builtin_bit_cast(s16x4, b),
-                                                        c, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                       0, 0, 0);
     } else {
-        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, a), __builtin_bit_cast(f16x4, b), c,
-                                                    0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c,
+                                                      0, 0, 0);
     }
 }
 
@@ -236,11 +243,9 @@ struct GqaCore {
                     // two accumulators halve the dependent MFMA chain over the head dim
                     f32x4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int c2 = 0; c2 < kKC; ++c2) {
-                        c0 = mfma16<DT>(make_uint2(kb[blk][c2].x, kb[blk][c2].y),
-                                        make_uint2(qb[mb][c2].x, qb[mb][c2].y), c0);
-                        c1 = mfma16<DT>(make_uint2(kb[blk][c2].z, kb[blk][c2].w),
-                                        make_uint2(qb[mb][c2].z, qb[mb][c2].w), c1);
+                    for (int c2 = 0; c2 < kKC; c2 += 2) {
+                        c0 = mfma32<DT>(kb[blk][c2], qb[mb][c2], c0);
+                        c1 = mfma32<DT>(kb[blk][c2 + 1], qb[mb][c2 + 1], c1);
                     }
                     f32x4 c = c0 + c1;
 #pragma unroll
@@ -290,13 +295,14 @@ struct GqaCore {
 #pragma unroll
                 for (int e = 0; e < kEV; ++e) {
                     const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-                    uint2 va;
-                    va.x = __builtin_amdgcn_perm(vb[blk][1].dword(e >> 1), vb[blk][0].dword(e >> 1), sel);
-                    va.y = __builtin_amdgcn_perm(vb[blk][3].dword(e >> 1), vb[blk][2].dword(e >> 1), sel);
+                    // contraction slots 0..3: the four tokens against P_hi, 4..7: the same tokens against P_lo
+                    const uint32_t v01 = __builtin_amdgcn_perm(vb[blk][1].dword(e >> 1), vb[blk][0].dword(e >> 1), sel);
+                    const uint32_t v23 = __builtin_amdgcn_perm(vb[blk][3].dword(e >> 1), vb[blk][2].dword(e >> 1), sel);
+                    const u32x4 va = {v01, v23, v01, v23};
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb) {
-                        acc[mb][e] = mfma16<DT>(va, p_hi[mb][blk], acc[mb][e]);
-                        acc[mb][e] = mfma16<DT>(va, p_lo[mb][blk], acc[mb][e]);
+                        const u32x4 pb = {p_hi[mb][blk].x, p_hi[mb][blk].y, p_lo[mb][blk].x, p_lo[mb][blk].y};
+                        acc[mb][e] = mfma32<DT>(va, pb, acc[mb][e]);
                     }
                 }
             }

@@ -54,6 +54,14 @@ def _check(got, got_lse, want, want_lse, label=""):
     max_abs, rel_l2 = oracle.error_metrics(got, want)
     assert max_abs <= MAX_ABS and rel_l2 <= REL_L2, f"{label}: max_abs={max_abs:.3e} rel_l2={rel_l2:.3e}"
     assert max_abs <= TIGHT_ABS and rel_l2 <= TIGHT_REL, f"{label}: (tight) max_abs={max_abs:.3e} rel_l2={rel_l2:.3e}"
+    # the worst single output row, against the same bars (an error confined to one head must not hide)
+    g2, w2 = np.asarray(got, dtype=np.float64).reshape(-1, got.shape[-1]), want.reshape(-1, want.shape[-1])
+    row_err = np.sqrt(((g2 - w2) ** 2).sum(axis=1))
+    row_norm = np.sqrt((w2 ** 2).sum(axis=1))
+    live = row_norm > 0
+    worst = float(np.max(row_err[live] / row_norm[live], initial=0.0))
+    assert worst <= 10 * TIGHT_REL, f"{label}: worst row rel_l2={worst:.3e}"
+    assert np.all(row_err[~live] == 0), f"{label}: a row that must be zero is not"
     if got_lse is not None:
         fin = np.isfinite(want_lse)
         assert np.array_equal(np.isneginf(got_lse), np.isneginf(want_lse)), f"{label}: lse -inf pattern"
