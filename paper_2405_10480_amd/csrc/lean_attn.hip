@@ -72,12 +72,10 @@ static Variant gqa_shape(int shape) {  // <16-token blocks per wave per step, wa
     }
 }
 
-// Two blocks of 16 query rows per pass over K/V (17..32 rows per output tile, D <= 128).  Only the
-// single-buffered shapes are built: the second set of accumulators takes the registers of the
-// second load buffer.
+// Two blocks of 16 query rows per pass over K/V (17..32 rows per output tile, D <= 128).
 template <int DT, int D>
 static Variant gqa_shape_two_blocks(int shape) {
-    if (shape == 0) shape = D == 64 ? 4 : 5;  // measured best: eight waves at D = 64, two token blocks at D = 128
+    if (shape == 0) shape = D == 64 ? 1 : 5;  // measured best: two token blocks per wave, double-buffered at D = 64
     switch (shape) {
         case 0: return variant_of<GqaCore<DT, D, 1, 4, false, 2>>();
         case 1: return variant_of<GqaCore<DT, D, 2, 4, true, 2>>();

@@ -477,3 +477,27 @@ def test_attend_error_paths():
     torch.cuda.synchronize()
     want, _ = _oracle_attend(inp)
     _check(out.cpu().numpy(), None, want, None, "after errors")
+
+
+def test_two_streams_with_their_own_workspaces_run_concurrently():
+    # calls in flight at the same time need separate workspaces, nothing else; each launch's
+    # workgroups only wait for lower ids of their own launch, so co-resident launches cannot block each other
+    inp_a = _mk(2, 16, 2, 128, "bf16", [40000, 999], workloads.KV_PADDED, seed=90)
+    inp_b = _mk(3, 8, 8, 64, "f16", [30000, 1, 5000], workloads.KV_PACKED, seed=91)
+    want_a, _ = _oracle(inp_a)
+    want_b, _ = _oracle(inp_b)
+    outs, wss, streams = [], [], [torch.cuda.Stream(), torch.cuda.Stream()]
+    for inp in (inp_a, inp_b):
+        w = inp.w
+        wss.append(_workspace(w.B, w.Hq, w.Hkv, w.D, la.F16 if w.dtype == "f16" else la.BF16))
+        outs.append(torch.full((w.B, w.Hq, w.D), float("nan"), dtype=torch.float32, device="cuda"))
+    torch.cuda.synchronize()
+    for rep in range(20):
+        for i, inp in enumerate((inp_a, inp_b)):
+            w = inp.w
+            la.lean_attn_decode(inp.q, inp.k, inp.v, inp.seqlens, outs[i], wss[i], Hkv=w.Hkv, kv_layout=w.kv_layout,
+                                kv_seq_stride=w.n_stride, scale=w.scale, stream=streams[i])
+    torch.cuda.synchronize()
+    assert la.lean_attn_workspace_status(wss[0]) == 0 and la.lean_attn_workspace_status(wss[1]) == 0
+    _check(outs[0].cpu().numpy(), None, want_a, None, "stream 0")
+    _check(outs[1].cpu().numpy(), None, want_b, None, "stream 1")
