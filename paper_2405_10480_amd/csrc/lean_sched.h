@@ -63,11 +63,19 @@ struct Segment {
     int64_t tile_iter_end;    // global iteration index one past the tile
 };
 
+// a / b for iteration counts (0 <= a <= I, 0 < b <= I + 1).  On the device a 64-bit division is
+// a long emulated sequence and the span walk needs several per segment, so iteration spaces
+// below 2^31 (all realistic ones) divide in 32 bits.
+LEAN_HD int64_t div_iters(const Sched& s, int64_t a, int64_t b) {
+    if (s.total_iters < 0x7fffffff) return (int64_t)((uint32_t)a / (uint32_t)b);
+    return a / b;
+}
+
 // The CTA whose span holds global iteration `it` (stream-K spans).
 LEAN_HD int cta_of_iter(const Sched& s, int64_t it) {
     const int64_t fat = (int64_t)s.extra * (s.iters_per_cta + 1);
-    if (it < fat) return (int)(it / (s.iters_per_cta + 1));
-    return s.extra + (int)((it - fat) / s.iters_per_cta);
+    if (it < fat) return (int)div_iters(s, it, s.iters_per_cta + 1);
+    return s.extra + (int)div_iters(s, it - fat, s.iters_per_cta);
 }
 
 // Largest b in [0, B) with cu_iters[b] <= key (key < cu_iters[B]); skips empty sequences.
@@ -87,18 +95,18 @@ LEAN_HD Segment locate(const Sched& s, const SchedTable& t, int64_t it, int64_t 
     int32_t c_n;
     if (s.packed) {
         const int64_t per_head = t.cu_iters[s.B];
-        sg.h = (int32_t)(it / per_head);
+        sg.h = (int32_t)div_iters(s, it, per_head);
         const int32_t key = (int32_t)(it - (int64_t)sg.h * per_head);
         sg.b = find_sequence(t, s.B, key);
         c_n = t.cu_iters[sg.b + 1] - t.cu_iters[sg.b];
         tile_iter = (int64_t)sg.h * per_head + t.cu_iters[sg.b];
         sg.tile_idx = sg.h * s.B + sg.b;
     } else {
-        const int32_t key = (int32_t)(it / s.Hkv);
+        const int32_t key = (int32_t)div_iters(s, it, s.Hkv);
         sg.b = find_sequence(t, s.B, key);
         c_n = t.cu_iters[sg.b + 1] - t.cu_iters[sg.b];
         const int64_t seq_iter = (int64_t)s.Hkv * t.cu_iters[sg.b];
-        sg.h = (int32_t)((it - seq_iter) / c_n);
+        sg.h = (int32_t)div_iters(s, it - seq_iter, c_n);
         tile_iter = seq_iter + (int64_t)sg.h * c_n;
         sg.tile_idx = sg.b * s.Hkv + sg.h;
     }

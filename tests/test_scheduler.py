@@ -288,3 +288,12 @@ def test_argument_errors():
     assert sz >= 256 + 4 * 4096 + 4096 * 8 * 130 * 4 and sz % 256 == 0
     for code in range(-9, 1):
         assert la.lean_attn_strerror(code) not in ("", "unknown status")
+
+
+@pytest.mark.parametrize("layout", [la.KV_PADDED, la.KV_PACKED])
+def test_span_invariants_beyond_two_to_the_31_iterations(layout):
+    # the span walk divides in 32 bits below 2^31 iterations and in 64 bits above: cover the latter
+    seqlens = [8388607 - 64 * i for i in range(200)]
+    p = _plan(seqlens, 128, 128, 128, la.BF16, layout, num_cus=16, ctas_per_cu=1, grid=16)
+    assert p.total_iters > 2 ** 31
+    _check_invariants(seqlens, 128, layout, p)
