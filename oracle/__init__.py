@@ -63,6 +63,12 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_int64, ctypes.c_double, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
         ]
+        lib.oracle_attention_ragged.restype = ctypes.c_int
+        lib.oracle_attention_ragged.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int64, ctypes.c_double, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+        ]
         _lib = lib
     return _lib
 
@@ -149,6 +155,37 @@ def attention(q, k, v, seqlens, *, N_q, Hq, Hkv, D, scale, causal, kv_layout=KV_
     if rc < 0:
         raise ValueError(f"oracle_attention rejected its arguments (code {rc})")
     return (out, lse, rc) if return_threads else (out, lse)
+
+
+def attention_ragged(q, k, v, seqlens, q_lens, *, Hq, Hkv, D, scale, causal, kv_layout=KV_PADDED, n_stride=0,
+                     dtype=None, threads=0):
+    """Exact attention with ``q_lens[b]`` query rows for sequence b (its last cached tokens).
+
+    q ``[sum(q_lens),Hq,D]`` (sequence after sequence); k, v as for :func:`decode_attention`.
+    With ``causal`` row i of sequence b attends to the first ``N_b - q_lens[b] + i + 1`` rows.
+    Returns ``(out[sum(q_lens),Hq,D], lse[sum(q_lens),Hq])``.
+    """
+    code = dtype_code_of(q) if dtype is None else dtype
+    qa, ka, va = (_as_host_array(t, code) for t in (q, k, v))
+    sl = np.ascontiguousarray(np.asarray(seqlens, dtype=np.int32))
+    ql = np.ascontiguousarray(np.asarray(q_lens, dtype=np.int32))
+    B = sl.shape[0]
+    assert ql.shape[0] == B, "one query length per sequence"
+    n_tok = int(ql.sum())
+    assert qa.size == n_tok * Hq * D, "q must be [sum(q_lens),Hq,D]"
+    total = int(sl.sum())
+    if kv_layout == KV_PADDED:
+        assert ka.size == B * Hkv * n_stride * D and va.size == ka.size, "k/v must be [B,Hkv,n_stride,D]"
+    else:
+        assert ka.size == Hkv * total * D and va.size == ka.size, "k/v must be [Hkv,sum(seqlens),D]"
+    out = np.empty((n_tok, Hq, D), dtype=np.float64)
+    lse = np.empty((n_tok, Hq), dtype=np.float64)
+    rc = _load().oracle_attention_ragged(
+        qa.ctypes.data, ka.ctypes.data, va.ctypes.data, sl.ctypes.data, ql.ctypes.data, B, Hq, Hkv, D, code,
+        kv_layout, int(n_stride), float(scale), int(bool(causal)), out.ctypes.data, lse.ctypes.data, int(threads))
+    if rc < 0:
+        raise ValueError(f"oracle_attention_ragged rejected its arguments (code {rc})")
+    return out, lse
 
 
 def attention_row(q, k, v, scale):

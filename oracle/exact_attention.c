@@ -99,37 +99,43 @@ static void attend_one(const void* q, int64_t q_off, const void* k_rows, const v
 
 /*
  * Query tiles (N_q >= 1 rows per sequence; Algorithm 2 counts C_m = ceil(N_q / T_m) output
- * tiles of them).  The N_q query tokens of sequence b are its LAST N_q cached tokens.
+ * tiles of them).  The query tokens of sequence b are its LAST q_len[b] cached tokens.
  *
- * q   : [B, N_q, Hq, D]
+ * q   : [sum_b q_len[b], Hq, D]: the query tokens of sequence 0, then of sequence 1, ...
+ *       (with every q_len[b] = N_q this is [B, N_q, Hq, D])
  * k,v : PADDED [B, Hkv, n_stride, D]  (row t of (b,h) at ((b*Hkv+h)*n_stride + t)*D), or
  *       PACKED [Hkv, total, D] with total = sum(seqlens), sequence b starting at
  *       row cu[b] = sum_{b'<b} seqlens[b'] (n_stride ignored)
  * causal = 0: every query row attends to all N_b cached rows.
- * causal = 1: query row i (0-based) is token N_b - N_q + i of its sequence and attends to
- *             the cached rows t <= N_b - N_q + i, i.e. to N_b - N_q + i + 1 rows.  (The paper
- *             does not discuss masking; this is the usual decoder mask aligned to the end of
- *             the context.)  Needs N_b >= N_q or N_b == 0.
- * out : [B, N_q, Hq, D] doubles;  lse: [B, N_q, Hq] doubles or NULL
+ * causal = 1: query row i (0-based) is token N_b - q_len[b] + i of its sequence and attends to
+ *             the cached rows t <= N_b - q_len[b] + i, i.e. to N_b - q_len[b] + i + 1 rows.  (The
+ *             paper does not discuss masking; this is the usual decoder mask aligned to the end of
+ *             the context.)  Needs N_b >= q_len[b] or N_b == 0.
+ * out : [sum_b q_len[b], Hq, D] doubles;  lse: [sum_b q_len[b], Hq] doubles or NULL
  * Returns the number of threads used, or a negative value for bad arguments.
  */
-int oracle_attention(const void* q, const void* k, const void* v, const int32_t* seqlens, int B,
-                     int N_q, int Hq, int Hkv, int D, int dtype, int kv_layout, int64_t n_stride,
-                     double scale, int causal, double* out, double* lse, int n_threads) {
-    if (!q || !k || !v || !seqlens || !out) return -1;
-    if (B <= 0 || N_q <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv != 0) return -2;
+int oracle_attention_ragged(const void* q, const void* k, const void* v, const int32_t* seqlens,
+                            const int32_t* q_lens, int B, int Hq, int Hkv, int D, int dtype,
+                            int kv_layout, int64_t n_stride, double scale, int causal, double* out,
+                            double* lse, int n_threads) {
+    if (!q || !k || !v || !seqlens || !q_lens || !out) return -1;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv != 0) return -2;
     if (dtype < 0 || dtype > 2 || kv_layout < 0 || kv_layout > 1) return -3;
-    int64_t total = 0, nmax = 0;
-    int64_t* cu = (int64_t*)malloc((size_t)(B + 1) * sizeof(int64_t));
+    int64_t total = 0, nmax = 0, q_total = 0;
+    int64_t* cu = (int64_t*)malloc((size_t)(2 * B + 2) * sizeof(int64_t));
     if (!cu) return -4;
+    int64_t* cu_q = cu + B + 1;
     for (int b = 0; b < B; ++b) {
-        if (seqlens[b] < 0) { free(cu); return -5; }
-        if (causal && seqlens[b] != 0 && seqlens[b] < N_q) { free(cu); return -7; }
+        if (seqlens[b] < 0 || q_lens[b] < 0) { free(cu); return -5; }
+        if (causal && seqlens[b] != 0 && seqlens[b] < q_lens[b]) { free(cu); return -7; }
         cu[b] = total;
+        cu_q[b] = q_total;
         total += seqlens[b];
+        q_total += q_lens[b];
         if (seqlens[b] > nmax) nmax = seqlens[b];
     }
     cu[B] = total;
+    cu_q[B] = q_total;
     if (kv_layout == ORACLE_KV_PADDED && n_stride < nmax) { free(cu); return -6; }
     const int group = Hq / Hkv;
     int used = 1;
@@ -146,15 +152,19 @@ int oracle_attention(const void* q, const void* k, const void* v, const int32_t*
 #ifdef _OPENMP
 #pragma omp for schedule(dynamic, 1)
 #endif
-        for (int64_t r = 0; r < (int64_t)B * N_q * Hq; ++r) {
-            int b = (int)(r / ((int64_t)N_q * Hq)), i = (int)((r / Hq) % N_q), hq = (int)(r % Hq);
+        for (int64_t r = 0; r < q_total * Hq; ++r) {
+            int64_t token = r / Hq; /* index into the concatenated query tokens */
+            int hq = (int)(r % Hq);
+            int b = 0;
+            while (cu_q[b + 1] <= token) ++b; /* the sequence that owns this query token */
+            int i = (int)(token - cu_q[b]);
             int h;
             h = hq / group;
             int64_t kv_off = kv_layout == ORACLE_KV_PADDED
                                  ? ((int64_t)(b * (int64_t)Hkv + h) * n_stride) * D
                                  : ((int64_t)h * total + cu[b]) * D;
             int64_t n_visible = seqlens[b];
-            if (causal && n_visible > 0) n_visible = n_visible - N_q + i + 1;
+            if (causal && n_visible > 0) n_visible = n_visible - q_lens[b] + i + 1;
             attend_one(q, r * D, k, v, kv_off, n_visible, D, dtype, scale, scores, row, qrow,
                        out + r * D, lse ? lse + r : NULL);
         }
@@ -166,6 +176,20 @@ int oracle_attention(const void* q, const void* k, const void* v, const int32_t*
 #endif
     free(cu);
     return used;
+}
+
+/* The same with N_q query tokens for every sequence: q, out [B, N_q, Hq, D], lse [B, N_q, Hq]. */
+int oracle_attention(const void* q, const void* k, const void* v, const int32_t* seqlens, int B,
+                     int N_q, int Hq, int Hkv, int D, int dtype, int kv_layout, int64_t n_stride,
+                     double scale, int causal, double* out, double* lse, int n_threads) {
+    if (B <= 0 || N_q <= 0) return -2;
+    int32_t* q_lens = (int32_t*)malloc((size_t)B * sizeof(int32_t));
+    if (!q_lens) return -4;
+    for (int b = 0; b < B; ++b) q_lens[b] = N_q;
+    int rc = oracle_attention_ragged(q, k, v, seqlens, q_lens, B, Hq, Hkv, D, dtype, kv_layout,
+                                     n_stride, scale, causal, out, lse, n_threads);
+    free(q_lens);
+    return rc;
 }
 
 /*

@@ -26,7 +26,9 @@ static_assert(kMaxGrid == LEAN_ATTN_MAX_GRID, "header and workspace layout disag
 // Shape 0 is the default, picked by the LeanTile sweep on MI355X (the paper fixes the tile
 // size per architecture after an empirical sweep, Section 4.2): with non-temporal loads the
 // memory system runs fastest with about 8 KiB in flight per wave and one workgroup per
-// compute unit of four waves, single-buffered: T_n = 64 tokens at D = 128 for both cores.
+// compute unit of four waves, single-buffered: T_n = 64 tokens at D = 128 for both cores.  The
+// MFMA core's bytes in flight scale with the row length, so its default is eight waves at
+// D = 64 and two token blocks per wave at D = 256 (see gqa_shape).
 constexpr int kDefaultCtasPerCu = 1;
 constexpr int kDefaultFanin = 8;
 constexpr int kDefaultGridMultiple = 1;

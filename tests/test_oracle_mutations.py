@@ -30,10 +30,14 @@ MUTANTS = {
     "dot_misses_last_element": ("for (int j = 0; j < D; ++j) dot += qrow[j] * row[j];", "for (int j = 0; j < D - (D > 1); ++j) dot += qrow[j] * row[j];"),
     "bf16_shift_wrong": ("uint32_t u = ((uint32_t)bits) << 16;", "uint32_t u = ((uint32_t)bits) << 15;"),
     "packed_offset_ignores_sequence_start": (": ((int64_t)h * total + cu[b]) * D;", ": ((int64_t)h * total) * D;"),
-    "causal_limit_off_by_one": ("n_visible = n_visible - N_q + i + 1;", "n_visible = n_visible - N_q + i + (n_visible - N_q + i > 0 ? 0 : 1);"),
-    "causal_mask_ignores_query_row": ("n_visible = n_visible - N_q + i + 1;", "n_visible = n_visible - N_q + 1;"),
-    "query_row_and_head_transposed": ("i = (int)((r / Hq) % N_q), hq = (int)(r % Hq);",
-                                      "i = (int)(r % N_q), hq = (int)((r / N_q) % Hq);"),
+    "causal_limit_off_by_one": ("n_visible = n_visible - q_lens[b] + i + 1;",
+                                "n_visible = n_visible - q_lens[b] + i + (n_visible - q_lens[b] + i > 0 ? 0 : 1);"),
+    "causal_mask_ignores_query_row": ("n_visible = n_visible - q_lens[b] + i + 1;", "n_visible = n_visible - q_lens[b] + 1;"),
+    "query_row_and_head_transposed": ("int64_t token = r / Hq; /* index into the concatenated query tokens */\n            int hq = (int)(r % Hq);",
+                                      "int64_t token = r % q_total;\n            int hq = (int)(r / q_total);"),
+    "query_offsets_assume_equal_lengths": ("cu_q[b] = q_total;", "cu_q[b] = (int64_t)b * q_lens[0];"),
+    "causal_mask_uses_the_longest_query": ("n_visible = n_visible - q_lens[b] + i + 1;",
+                                           "n_visible = n_visible - q_lens[0] + i + 1;"),
     "padded_offset_ignores_head": ("? ((int64_t)(b * (int64_t)Hkv + h) * n_stride) * D", "? ((int64_t)(b * (int64_t)Hkv) * n_stride) * D"),
 }
 
@@ -51,6 +55,8 @@ def _compile(tmp_path, name, old, new):
     dll.oracle_decode_attention.argtypes = oracle._load().oracle_decode_attention.argtypes
     dll.oracle_attention.restype = ctypes.c_int
     dll.oracle_attention.argtypes = oracle._load().oracle_attention.argtypes
+    dll.oracle_attention_ragged.restype = ctypes.c_int
+    dll.oracle_attention_ragged.argtypes = oracle._load().oracle_attention_ragged.argtypes
     return dll
 
 
@@ -126,6 +132,33 @@ def _pins_hold(dll) -> bool:
                     return False
                 if np.max(np.abs(lse[0] - np.log(np.array(case[f"lse_{tag}_log_of"])))) > 1e-12:
                     return False
+        # per-sequence query lengths against the masked score matrix, sequence by sequence
+        r = np.random.default_rng(3)
+        B, Hq, Hkv, D = 3, 2, 1, 3
+        lens, q_lens = [5, 4, 6], [3, 1, 2]
+        nmax = max(lens)
+        q = r.normal(size=(sum(q_lens), Hq, D))
+        k = r.normal(size=(B, Hkv, nmax, D))
+        v = r.normal(size=(B, Hkv, nmax, D))
+        sl = np.asarray(lens, dtype=np.int32)
+        ql = np.asarray(q_lens, dtype=np.int32)
+        out = np.empty((sum(q_lens), Hq, D))
+        lse = np.empty((sum(q_lens), Hq))
+        rc = dll.oracle_attention_ragged(q.ctypes.data, k.ctypes.data, v.ctypes.data, sl.ctypes.data, ql.ctypes.data, B,
+                                         Hq, Hkv, D, oracle.F64, 0, nmax, 0.6, 1, out.ctypes.data, lse.ctypes.data, 1)
+        if rc <= 0:
+            return False
+        start = 0
+        for b in range(B):
+            n, nq = lens[b], q_lens[b]
+            for h in range(Hq):
+                S = 0.6 * q[start:start + nq, h] @ k[b, 0, :n].T
+                S = np.where(np.arange(n)[None, :] <= np.arange(nq)[:, None] + (n - nq), S, -np.inf)
+                P = np.exp(S - S.max(axis=1, keepdims=True))
+                want = (P / P.sum(axis=1, keepdims=True)) @ v[b, 0, :n]
+                if np.max(np.abs(out[start:start + nq, h] - want)) > 1e-12:
+                    return False
+            start += nq
         # bf16 widening: q = 1.0, one token, v carries the pattern
         bits = np.array([0x3F80, 0x4049, 0xC2F7, 0x0080, 0x3EAA], dtype=np.uint16)
         want = (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)

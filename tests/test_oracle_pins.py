@@ -471,3 +471,68 @@ def test_causal_query_tile_longer_than_its_context_is_rejected():
     out, _ = oracle.attention(x, kv, kv, [2], N_q=3, Hq=1, Hkv=1, D=2, scale=1.0, causal=False, n_stride=2,
                               dtype=oracle.F64)
     assert out.shape == (1, 3, 1, 2)
+
+
+# ---------------------------------------------------------------- per-sequence query lengths
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("layout", [oracle.KV_PADDED, oracle.KV_PACKED])
+def test_ragged_query_lengths_against_masked_score_matrix(causal, layout):
+    # a prefill chunk, decode steps, a sequence without queries and an empty context in one batch
+    r = _rng(50 + int(causal))
+    B, Hq, Hkv, D = 5, 4, 2, 6
+    lens = [9, 5, 7, 0, 3]
+    q_lens = [4, 1, 0, 2, 3]
+    nmax, scale = max(lens), 0.45
+    q = r.normal(size=(sum(q_lens), Hq, D))
+    k = r.normal(size=(B, Hkv, nmax, D))
+    v = r.normal(size=(B, Hkv, nmax, D))
+    if layout == oracle.KV_PACKED:
+        kk = np.ascontiguousarray(np.concatenate([k[b, :, :lens[b]] for b in range(B)], axis=1))
+        vv = np.ascontiguousarray(np.concatenate([v[b, :, :lens[b]] for b in range(B)], axis=1))
+    else:
+        kk, vv = k, v
+    out, lse = oracle.attention_ragged(q, kk, vv, lens, q_lens, Hq=Hq, Hkv=Hkv, D=D, scale=scale, causal=causal,
+                                       kv_layout=layout, n_stride=nmax, dtype=oracle.F64)
+    assert out.shape == (sum(q_lens), Hq, D)
+    start, group = 0, Hq // Hkv
+    for b in range(B):
+        n, nq = lens[b], q_lens[b]
+        rows = slice(start, start + nq)
+        start += nq
+        if n == 0:
+            assert np.all(out[rows] == 0) and np.all(np.isneginf(lse[rows]))
+            continue
+        for hq in range(Hq):
+            S = scale * q[rows, hq] @ k[b, hq // group, :n].T
+            if causal:
+                S = np.where(np.arange(n)[None, :] <= np.arange(nq)[:, None] + (n - nq), S, -np.inf)
+            P = np.exp(S - S.max(axis=1, keepdims=True))
+            np.testing.assert_allclose(out[rows, hq], (P / P.sum(axis=1, keepdims=True)) @ v[b, hq // group, :n],
+                                       rtol=0, atol=1e-13)
+            np.testing.assert_allclose(lse[rows, hq], S.max(axis=1) + np.log(P.sum(axis=1)), rtol=0, atol=1e-13)
+
+
+def test_ragged_query_lengths_reduce_to_the_uniform_and_single_sequence_forms():
+    r = _rng(52)
+    B, Hq, Hkv, D = 3, 2, 2, 4
+    lens, nmax = [6, 8, 5], 8
+    k = r.normal(size=(B, Hkv, nmax, D))
+    v = r.normal(size=(B, Hkv, nmax, D))
+    kw = dict(Hq=Hq, Hkv=Hkv, D=D, scale=0.5, causal=True, n_stride=nmax, dtype=oracle.F64)
+    # equal lengths: the [B, N_q, ...] form
+    q = r.normal(size=(B, 3, Hq, D))
+    a, al = oracle.attention_ragged(q.reshape(B * 3, Hq, D), k, v, lens, [3, 3, 3], **kw)
+    u, ul = oracle.attention(q, k, v, lens, N_q=3, **kw)
+    assert np.array_equal(a.reshape(u.shape), u) and np.array_equal(al.reshape(ul.shape), ul)
+    # unequal lengths: every sequence on its own
+    q_lens = [2, 5, 1]
+    q = r.normal(size=(sum(q_lens), Hq, D))
+    a, al = oracle.attention_ragged(q, k, v, lens, q_lens, **kw)
+    start = 0
+    for b in range(B):
+        one, one_l = oracle.attention(q[start:start + q_lens[b]][None], k[b:b + 1], v[b:b + 1], [lens[b]],
+                                      N_q=q_lens[b], **kw)
+        assert np.array_equal(a[start:start + q_lens[b]], one[0]) and np.array_equal(al[start:start + q_lens[b]], one_l[0])
+        start += q_lens[b]
+    with pytest.raises(ValueError):   # causal: more query rows than cached tokens
+        oracle.attention_ragged(r.normal(size=(13, Hq, D)), k, v, lens, [2, 5, 6], **kw)
