@@ -147,6 +147,13 @@ typedef struct lean_attn_problem {
     int32_t causal;        /* 0 or 1 */
     float scale;           /* multiplies q.k before the softmax */
     int64_t kv_seq_stride; /* PADDED layout: rows between consecutive (b, h) slabs */
+    const int32_t* q_lens; /* HOST, B entries, or NULL.  Per-sequence query lengths (mixed prefill and
+                              decode batches): sequence b has q_lens[b] in [0, N_q] query rows, its last
+                              q_lens[b] cached tokens, and N_q must equal the longest.  q, out and lse
+                              are then packed: [sum_b q_lens[b], Hq, ...], sequence after sequence.
+                              The schedule is that of N_q rows for every sequence; the row blocks a
+                              shorter sequence does not reach are skipped (their K/V is not read),
+                              which unbalances the spans once N_q * Hq / Hkv exceeds one output tile. */
 } lean_attn_problem;
 
 /*
@@ -227,11 +234,12 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache,
 /*
  * Attention of short query tiles over the KV cache (Algorithm 2 with C_m >= 1).
  *   problem  host, see lean_attn_problem
- *   q        device, [B, N_q, Hq, D], 16-bit elements of problem->dtype, contiguous
+ *   q        device, [B, N_q, Hq, D] (packed [sum q_lens, Hq, D] with problem->q_lens), 16-bit
+ *            elements of problem->dtype, contiguous
  *   k_cache, v_cache, seqlens, workspace, tuning, hip_stream  as for lean_attn_decode;
  *            the workspace size comes from lean_attn_problem_workspace_size
- *   out      device, [B, N_q, Hq, D], fp32 or 16-bit per problem->out_dtype
- *   lse      device, [B, N_q, Hq] fp32, or NULL
+ *   out      device, shaped like q, fp32 or 16-bit per problem->out_dtype
+ *   lse      device, [B, N_q, Hq] ([sum q_lens, Hq]) fp32, or NULL
  * Rows of a sequence with N_b = 0 get out = 0, lse = -inf.
  */
 int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void* k_cache,

@@ -38,8 +38,22 @@ class Problem(ctypes.Structure):
         ("B", ctypes.c_int32), ("N_q", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
         ("D", ctypes.c_int32), ("dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
         ("kv_layout", ctypes.c_int32), ("causal", ctypes.c_int32), ("scale", ctypes.c_float),
-        ("kv_seq_stride", ctypes.c_int64),
+        ("kv_seq_stride", ctypes.c_int64), ("q_lens", ctypes.c_void_p),
     ]
+
+    def set_q_lens(self, q_lens: Optional[Sequence[int]]) -> "Problem":
+        """Per-sequence query lengths (host array kept alive by this object); ``None`` clears them."""
+        if q_lens is None:
+            self._q_lens_host, self._q_lens_list, self.q_lens = None, None, None
+            return self
+        arr = (ctypes.c_int32 * len(q_lens))(*[int(x) for x in q_lens])
+        self._q_lens_host, self._q_lens_list = arr, [int(x) for x in q_lens]
+        self.q_lens = ctypes.cast(arr, ctypes.c_void_p).value
+        return self
+
+    def query_tokens(self) -> int:
+        lens = getattr(self, "_q_lens_list", None)
+        return int(sum(lens)) if lens is not None else int(self.B) * int(self.N_q)
 
 
 class Tuning(ctypes.Structure):
@@ -236,9 +250,9 @@ def lean_attn_attend(problem: Problem, q, k_cache, v_cache, seqlens, out, worksp
         raise ValueError("q, k_cache, v_cache, out and workspace must be device tensors")
     if not (q.is_contiguous() and k_cache.is_contiguous() and v_cache.is_contiguous() and out.is_contiguous()):
         raise ValueError("tensors must be contiguous")
-    n_rows = p.B * p.N_q * p.Hq
+    n_rows = p.query_tokens() * p.Hq
     if q.numel() != n_rows * p.D or out.numel() != n_rows * p.D:
-        raise ValueError("q and out must be [B, N_q, Hq, D]")
+        raise ValueError("q and out must be [B, N_q, Hq, D] (or [sum(q_lens), Hq, D])")
     if _dtype_code(q) != p.dtype or k_cache.dtype != q.dtype or v_cache.dtype != q.dtype:
         raise ValueError("q, k_cache and v_cache must have the problem's element type")
     want_out = q.dtype if p.out_dtype == OUT_AS_INPUT else "torch.float32"
@@ -255,7 +269,7 @@ def lean_attn_attend(problem: Problem, q, k_cache, v_cache, seqlens, out, worksp
     elif k_cache.numel() != p.Hkv * total * p.D:
         raise ValueError("PACKED k_cache must be [Hkv, sum(seqlens), D]")
     if lse is not None and (str(lse.dtype) != "torch.float32" or lse.numel() != n_rows or not lse.is_cuda):
-        raise ValueError("lse must be a float32 device tensor [B, N_q, Hq]")
+        raise ValueError("lse must be a float32 device tensor [B, N_q, Hq] (or [sum(q_lens), Hq])")
     rc = _load().lean_attn_attend(
         ctypes.byref(p), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), _seqlens_array(seqlens),
         out.data_ptr(), lse.data_ptr() if lse is not None else None, workspace.data_ptr(),

@@ -150,6 +150,14 @@ static int check_problem(const lean_attn_problem& p) {
     if (p.B <= 0 || p.N_q <= 0 || p.Hq <= 0 || p.Hkv <= 0 || p.Hq % p.Hkv != 0) return LEAN_ATTN_ERR_BAD_SHAPE;
     if ((int64_t)p.N_q * (p.Hq / p.Hkv) > LEAN_ATTN_MAX_QUERY_ROWS) return LEAN_ATTN_ERR_BAD_SHAPE;
     if (p.causal != 0 && p.causal != 1) return LEAN_ATTN_ERR_BAD_SHAPE;
+    if (p.q_lens) {
+        int longest = 0;
+        for (int b = 0; b < p.B && b < LEAN_ATTN_MAX_BATCH; ++b) {
+            if (p.q_lens[b] < 0 || p.q_lens[b] > p.N_q) return LEAN_ATTN_ERR_BAD_SHAPE;
+            if (p.q_lens[b] > longest) longest = p.q_lens[b];
+        }
+        if (longest != p.N_q) return LEAN_ATTN_ERR_BAD_SHAPE;  // N_q is the longest query, by definition
+    }
     if (p.B > LEAN_ATTN_MAX_BATCH) return LEAN_ATTN_ERR_BATCH_TOO_LARGE;
     if (dim_index(p.D) < 0) return LEAN_ATTN_ERR_UNSUPPORTED;
     if (p.dtype != LEAN_ATTN_F16 && p.dtype != LEAN_ATTN_BF16) return LEAN_ATTN_ERR_UNSUPPORTED;
@@ -210,9 +218,10 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
         t.tile_shape >= kNumShapes || t.grid_multiple < 0 || t.fixed_split < -1)
         return LEAN_ATTN_ERR_TUNING;
     const int T_m = rb.T_m;
-    int kernel = rb.R == 1 ? 0 : 1;
+    // the single-row core indexes q and out by (b, head): per-sequence query lengths go to the MFMA core
+    int kernel = (rb.R == 1 && !p.q_lens) ? 0 : 1;
     if (t.kernel == 1) {
-        if (rb.R != 1) return LEAN_ATTN_ERR_TUNING;
+        if (rb.R != 1 || p.q_lens) return LEAN_ATTN_ERR_TUNING;
         kernel = 0;
     } else if (t.kernel == 2) {
         kernel = 1;
@@ -221,14 +230,17 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
     if (!pick_variant(kernel, dtype, D, t.tile_shape, T_m, &var)) return LEAN_ATTN_ERR_UNSUPPORTED;
     const int T_n = var.T_n;
 
-    int64_t iters = 0, toks = 0;
+    int64_t iters = 0, toks = 0, q_toks = 0;
     for (int b = 0; b < B; ++b) {
         if (seqlens[b] < 0) return LEAN_ATTN_ERR_SEQLEN;
-        if (p.causal && seqlens[b] != 0 && seqlens[b] < p.N_q) return LEAN_ATTN_ERR_SEQLEN;
+        const int q_len = p.q_lens ? p.q_lens[b] : p.N_q;
+        if (p.causal && seqlens[b] != 0 && seqlens[b] < q_len) return LEAN_ATTN_ERR_SEQLEN;
         if (table) {
             table->cu_iters[b] = (int32_t)iters;
             table->cu_tok[b] = (int32_t)toks;
+            table->cu_q[b] = (int32_t)q_toks;
         }
+        q_toks += q_len;
         if ((int64_t)seqlens[b] * D * 2 > INT32_MAX) return LEAN_ATTN_ERR_SEQLEN;  // one slab per buffer descriptor
         iters += ((int64_t)seqlens[b] + T_n - 1) / T_n;
         toks += seqlens[b];
@@ -237,6 +249,7 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
     if (table) {
         table->cu_iters[B] = (int32_t)iters;
         table->cu_tok[B] = (int32_t)toks;
+        table->cu_q[B] = (int32_t)q_toks;
     }
     const int64_t I = iters * heads;
 
@@ -434,8 +447,9 @@ int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void
     hipStream_t stream = (hipStream_t)hip_stream;
     const int out16 = p.out_dtype == LEAN_ATTN_OUT_AS_INPUT;
     if (plan.total_iters == 0) {  // every sequence is empty
-        const int64_t rows = (int64_t)B * p.N_q * p.Hq;
+        const int64_t rows = (int64_t)a.table.cu_q[B] * p.Hq;
         const int row_words = out16 ? D / 2 : D;
+        if (rows == 0) return LEAN_ATTN_OK;
         hipLaunchKernelGGL(lean_zero_rows_kernel, dim3((unsigned)((rows * row_words + 255) / 256)), dim3(256), 0,
                            stream, (uint32_t*)out, lse, rows, row_words);
         return hipGetLastError() == hipSuccess ? LEAN_ATTN_OK : LEAN_ATTN_ERR_HIP;
@@ -459,6 +473,7 @@ int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void
     a.Hq = p.Hq;
     a.Hkv = p.Hkv;
     a.N_q = p.N_q;
+    a.ragged_q = p.q_lens ? 1 : 0;
     a.group = p.Hq / p.Hkv;
     a.rows = rb.R;
     a.C_m = rb.C_m;

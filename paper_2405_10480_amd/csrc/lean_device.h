@@ -36,7 +36,8 @@ struct DecodeArgs {
     int64_t total_rows;    // PACKED: sum of N_b
     int32_t Hq;
     int32_t Hkv;           // KV heads (the schedule counts Hkv * C_m output tiles per sequence)
-    int32_t N_q;           // query tokens per sequence: the last N_q cached tokens
+    int32_t N_q;           // query tokens per sequence: the last N_q cached tokens (the maximum if ragged_q)
+    int32_t ragged_q;      // per-sequence query lengths: q, out, lse are packed by table.cu_q
     int32_t group;         // Hq / Hkv
     int32_t rows;          // N_q * group query rows share one KV head; row rho = token*group + head
     int32_t C_m;           // row blocks per KV head, ceil(rows / 16)
@@ -56,22 +57,33 @@ struct DecodeArgs {
 
 // The rows of output tile (b, head) where head = hk * C_m + mb: KV head hk, row block mb.
 struct TileRows {
-    int hk;     // KV head
-    int rho0;   // first row of the block within the KV head's rows
-    int count;  // rows in the block
+    int hk;      // KV head
+    int rho0;    // first row of the block within the KV head's rows
+    int count;   // rows in the block; <= 0 when the sequence has too few query tokens for this block
+    int q_len;   // query tokens of the sequence
+    int64_t q0;  // index of the sequence's first query token among all query tokens
 };
-__device__ __forceinline__ TileRows tile_rows(const DecodeArgs& a, int head) {
+__device__ __forceinline__ TileRows tile_rows(const DecodeArgs& a, int b, int head) {
     TileRows t;
     t.hk = a.C_m == 1 ? head : head / a.C_m;
     t.rho0 = (head - t.hk * a.C_m) * a.T_m;
-    t.count = a.rows - t.rho0 < a.T_m ? a.rows - t.rho0 : a.T_m;
+    if (a.ragged_q) {
+        t.q0 = a.table.cu_q[b];
+        t.q_len = a.table.cu_q[b + 1] - a.table.cu_q[b];
+    } else {
+        t.q0 = (int64_t)b * a.N_q;
+        t.q_len = a.N_q;
+    }
+    const int rows = a.ragged_q ? t.q_len * a.group : a.rows;
+    t.count = rows - t.rho0 < a.T_m ? rows - t.rho0 : a.T_m;
     return t;
 }
-// Index into q / out / lse rows ([B, N_q, Hq]) of row rho of KV head hk; *token gets the query token.
-__device__ __forceinline__ int64_t query_row(const DecodeArgs& a, int b, int hk, int rho, int* token) {
-    const int i = a.N_q == 1 ? 0 : rho / a.group;
+// Index into the q / out / lse rows (query token, query head) of row rho of the tile's KV head;
+// *token gets the query token within its sequence.
+__device__ __forceinline__ int64_t query_row(const DecodeArgs& a, const TileRows& t, int rho, int* token) {
+    const int i = (a.N_q == 1 && !a.ragged_q) ? 0 : rho / a.group;
     *token = i;
-    return ((int64_t)b * a.N_q + i) * a.Hq + (int64_t)hk * a.group + (rho - i * a.group);
+    return (t.q0 + i) * a.Hq + (int64_t)t.hk * a.group + (rho - i * a.group);
 }
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -85,7 +97,6 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 __device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
 
-// The two 16-bit elements packed in one dword, widened to fp32 (low half first).
 // Two fp32 values rounded to nearest-even 16-bit elements, packed low half first.
 template <int DT>
 __device__ __forceinline__ uint32_t narrow2(float lo, float hi) {
@@ -98,6 +109,7 @@ __device__ __forceinline__ uint32_t narrow2(float lo, float hi) {
     }
 }
 
+// The two 16-bit elements packed in one dword, widened to fp32 (low half first).
 template <int DT>
 __device__ __forceinline__ void widen2(uint32_t u, float& lo, float& hi) {
     if constexpr (DT == kDtBF16) {

@@ -137,7 +137,7 @@ struct GqaCore {
         const int r = lane & 15;   // A row / B column index of the lane
         const int g = lane >> 4;   // k-group of the lane
         const int n_ctx = sg.n_ctx;
-        const TileRows tr = tile_rows(a, sg.h);
+        const TileRows tr = tile_rows(a, sg.b, sg.h);
 
         const int64_t row0 = a.sched.packed
                                  ? (int64_t)tr.hk * a.total_rows + a.table.cu_tok[sg.b]
@@ -166,8 +166,8 @@ struct GqaCore {
             n_vis[mb] = n_ctx;
             if (16 * mb + r < tr.count) {
                 int token;
-                const int64_t qrow = query_row(a, sg.b, tr.hk, tr.rho0 + 16 * mb + r, &token);
-                if (a.causal) n_vis[mb] = n_ctx - a.N_q + token + 1;
+                const int64_t qrow = query_row(a, tr, tr.rho0 + 16 * mb + r, &token);
+                if (a.causal) n_vis[mb] = n_ctx - tr.q_len + token + 1;
                 const u32x4* qp = reinterpret_cast<const u32x4*>(a.q + qrow * D) + g;
 #pragma unroll
                 for (int c2 = 0; c2 < kKC; ++c2) qb[mb][c2] = qp[4 * c2];

@@ -114,14 +114,14 @@ __device__ __forceinline__ void reduce_tile(const DecodeArgs& a, OwnPartial<CPT>
         signal_arrival(a.flags + g);
     } else {
         // m is kept in the base-2 domain: L = ln2 * (m + log2 l)
-        const TileRows tr = tile_rows(a, h);
+        const TileRows tr = tile_rows(a, b, h);
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
             const int c = tid + i * THREADS;
             const int row = (4 * c) / D, col = (4 * c) % D;
             if (c < n_chunks && row < tr.count) {
                 int token;
-                const int64_t orow = query_row(a, b, tr.hk, tr.rho0 + row, &token);
+                const int64_t orow = query_row(a, tr, tr.rho0 + row, &token);
                 const f32x4 o = own.o[i] * (1.f / own.l[i]);
                 if (a.out16) {
                     *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(a.out) + orow * D + col) =
@@ -157,12 +157,12 @@ __global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_d
     // of small batches hit the scalar cache.
     asm volatile("" ::"s"(a.q), "s"(a.k), "s"(a.v), "s"(a.out), "s"(a.lse), "s"(a.status), "s"(a.flags),
                  "s"(a.partials), "s"(a.kv_seq_stride), "s"(a.total_rows), "s"(a.cta_clock), "s"(a.sched.total_iters),
-                 "s"(a.sched.iters_per_cta), "s"(a.Hq), "s"(a.Hkv), "s"(a.N_q), "s"(a.group), "s"(a.rows), "s"(a.C_m),
+                 "s"(a.sched.iters_per_cta), "s"(a.Hq), "s"(a.Hkv), "s"(a.N_q), "s"(a.ragged_q), "s"(a.group), "s"(a.rows),
+                 "s"(a.C_m),
                  "s"(a.T_m), "s"(a.causal), "s"(a.out16), "s"(a.slot), "s"(a.xcd_remap), "s"(a.spin_limit),
-                 "s"(a.has_empty), "s"(a.fanin), "s"(as_u32(a.scale_log2e)), "s"(a.table.cu_iters[1]),
-                 "s"(a.table.cu_tok[1]));
+                 "s"(a.has_empty), "s"(a.fanin), "s"(as_u32(a.scale_log2e)));
     asm volatile("" ::"s"(a.sched.B), "s"(a.sched.Hkv), "s"(a.sched.T_n), "s"(a.sched.packed), "s"(a.sched.grid),
-                 "s"(a.sched.extra), "s"(a.sched.fixed_split));
+                 "s"(a.sched.extra), "s"(a.sched.fixed_split), "s"(a.table.cu_iters[1]), "s"(a.table.cu_tok[1]));
 
     // CTA id.  The hardware deals consecutive workgroup ids round-robin to the
     // 8 XCDs; the optional remap makes the spans of one XCD contiguous so that
@@ -177,13 +177,14 @@ __global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_d
     stamp(a, g, 0);
 
     if (a.has_empty) {  // sequences with N_b = 0 own no iteration: their rows are defined as zero
-        const int rows_per_seq = a.N_q * a.Hq;
         const int row_words = a.out16 ? D / 2 : D;  // zero bits are 0.0 in every output type
-        for (int row = g; row < a.sched.B * rows_per_seq; row += G) {
-            const int b = row / rows_per_seq;
-            if (a.table.cu_tok[b + 1] == a.table.cu_tok[b]) {
+        for (int b = 0; b < a.sched.B; ++b) {
+            if (a.table.cu_tok[b + 1] != a.table.cu_tok[b]) continue;
+            const int64_t first = (a.ragged_q ? (int64_t)a.table.cu_q[b] : (int64_t)b * a.N_q) * a.Hq;
+            const int64_t last = (a.ragged_q ? (int64_t)a.table.cu_q[b + 1] : (int64_t)(b + 1) * a.N_q) * a.Hq;
+            for (int64_t row = first + g; row < last; row += G) {
                 for (int c = tid; c < row_words; c += THREADS)
-                    reinterpret_cast<uint32_t*>(a.out)[(int64_t)row * row_words + c] = 0u;
+                    reinterpret_cast<uint32_t*>(a.out)[row * row_words + c] = 0u;
                 if (a.lse && tid == 0) a.lse[row] = -INFINITY;
             }
         }
@@ -199,6 +200,12 @@ __global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_d
     while (it < cta_end) {
         const Segment sg = locate(a.sched, a.table, it, cta_end);
         if (it == cta_start) stamp(a, g, 2);
+        if (a.ragged_q && tile_rows(a, sg.b, sg.h).count <= 0) {
+            // a sequence with fewer query tokens than the longest: this row block holds no rows.
+            // Every CTA of the tile sees the same count, so none computes, publishes or waits.
+            it = sg.tile_iter_end;
+            continue;
+        }
         Core::run(a, sg, sm, g);  // ends with a workgroup barrier
 
         // Fold the per-wave partial streams into the workgroup's partial.

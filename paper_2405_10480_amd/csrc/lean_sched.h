@@ -34,6 +34,7 @@ constexpr int kMaxBatch = 256;
 struct SchedTable {
     int32_t cu_iters[kMaxBatch + 1];  // cuC[b] = sum_{b'<b} ceil(N_b' / T_n)
     int32_t cu_tok[kMaxBatch + 1];    // sum_{b'<b} N_b'
+    int32_t cu_q[kMaxBatch + 1];      // sum_{b'<b} query tokens of b' (read only with per-sequence query lengths)
 };
 
 struct Sched {

@@ -501,3 +501,70 @@ def test_two_streams_with_their_own_workspaces_run_concurrently():
     assert la.lean_attn_workspace_status(wss[0]) == 0 and la.lean_attn_workspace_status(wss[1]) == 0
     _check(outs[0].cpu().numpy(), None, want_a, None, "stream 0")
     _check(outs[1].cpu().numpy(), None, want_b, None, "stream 1")
+
+
+# ------------------------------------------------------------------ per-sequence query lengths (mixed batches)
+def _run_ragged(inp, tuning=None, out_dtype=la.OUT_F32):
+    w = inp.w
+    pr = _problem_of(w, out_dtype).set_q_lens(list(w.q_lens))
+    ws = torch.empty(la.lean_attn_problem_workspace_size(pr), dtype=torch.uint8, device="cuda")
+    la.lean_attn_workspace_init(ws)
+    n_tok = int(sum(w.q_lens))
+    odt = torch.float32 if out_dtype == la.OUT_F32 else w.torch_dtype
+    out = torch.full((n_tok, w.Hq, w.D), float("nan"), dtype=odt, device="cuda")
+    lse = torch.full((n_tok, w.Hq), float("nan"), dtype=torch.float32, device="cuda")
+    la.lean_attn_attend(pr, inp.q, inp.k, inp.v, inp.seqlens, out, ws, lse=lse, tuning=tuning)
+    torch.cuda.synchronize()
+    assert la.lean_attn_workspace_status(ws) == 0
+    return out, lse.cpu().numpy()
+
+
+def _oracle_ragged(inp):
+    w = inp.w
+    return oracle.attention_ragged(inp.q, inp.k, inp.v, inp.seqlens, list(w.q_lens), Hq=w.Hq, Hkv=w.Hkv, D=w.D,
+                                   scale=w.scale, causal=w.causal, kv_layout=w.kv_layout, n_stride=w.n_stride)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("D", [64, 128, 256])
+@pytest.mark.parametrize("group", [1, 4, 8])
+def test_mixed_prefill_and_decode_batch(causal, D, group):
+    # a prefill chunk, decode steps, a sequence without queries, an empty context, a chunk that is the whole context
+    Hkv = 2
+    q_lens = [7, 1, 0, 3, 1, 12]
+    seqlens = [900, 3000, 500, 0, 1, 12]
+    for layout in (workloads.KV_PADDED, workloads.KV_PACKED):
+        w = workloads.Workload(f"mixed_g{group}_d{D}", len(seqlens), Hkv * group, Hkv, D, "bf16", tuple(seqlens), layout,
+                               seed=95 + group, N_q=max(q_lens), causal=causal, q_lens=tuple(q_lens))
+        inp = workloads.generate(w, device="cuda")
+        want, want_lse = _oracle_ragged(inp)
+        for tn in (None, la.Tuning(grid=37, merge_fanin=3)):
+            got, got_lse = _run_ragged(inp, tn)
+            _check(got.cpu().numpy(), got_lse, want, want_lse, f"mixed g={group} D={D} causal={causal} layout={layout}")
+        # rows of the sequence with an empty context
+        first = sum(q_lens[:3])
+        assert torch.all(got[first:first + 3] == 0) and np.all(np.isneginf(got_lse[first:first + 3]))
+
+
+def test_mixed_batch_long_contexts_and_sixteen_bit_output():
+    # 64 rows per KV head at the longest (two output tiles), decode sequences reach only the first
+    Hkv, group, D = 2, 8, 128
+    q_lens = [8, 1, 1, 3]
+    seqlens = [30000, 52001, 777, 4100]
+    w = workloads.Workload("mixed_long", 4, Hkv * group, Hkv, D, "bf16", tuple(seqlens), workloads.KV_PACKED, seed=99,
+                           N_q=8, causal=True, q_lens=tuple(q_lens), outlier_frac=0.01)
+    inp = workloads.generate(w, device="cuda")
+    want, want_lse = _oracle_ragged(inp)
+    got, got_lse = _run_ragged(inp)
+    _check(got.cpu().numpy(), got_lse, want, want_lse, "mixed long")
+    got16, _ = _run_ragged(inp, out_dtype=la.OUT_AS_INPUT)
+    assert torch.equal(got16, got.to(torch.bfloat16))
+    # uniform lengths through the per-sequence path give the [B, N_q, ...] result bit for bit
+    wu = workloads.Workload("uniform", 2, 8, 2, 128, "bf16", (5000, 300), workloads.KV_PADDED, seed=98, N_q=3, causal=True)
+    inp_u = workloads.generate(wu, device="cuda")
+    a, a_lse = _run_attend(inp_u)
+    wr = workloads.Workload("uniform_r", 2, 8, 2, 128, "bf16", (5000, 300), workloads.KV_PADDED, seed=98, N_q=3, causal=True,
+                            q_lens=(3, 3))
+    inp_r = workloads.Inputs(wr, inp_u.q.reshape(6, 8, 128), inp_u.k, inp_u.v, list(wr.seqlens))
+    b, b_lse = _run_ragged(inp_r)
+    assert torch.equal(a.reshape(6, 8, 128), b) and np.array_equal(a_lse.reshape(6, 8), b_lse)

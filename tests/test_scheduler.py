@@ -297,3 +297,23 @@ def test_span_invariants_beyond_two_to_the_31_iterations(layout):
     p = _plan(seqlens, 128, 128, 128, la.BF16, layout, num_cus=16, ctas_per_cu=1, grid=16)
     assert p.total_iters > 2 ** 31
     _check_invariants(seqlens, 128, layout, p)
+
+
+def test_per_sequence_query_lengths_are_validated():
+    tn = la.Tuning(num_cus=4)
+    def status(pr, seqlens):
+        with pytest.raises(la.LeanAttnError) as e:
+            la.lean_attn_problem_schedule(pr, seqlens, tn)
+        return e.value.status
+    ok = _problem(3, 4, 8, 2, 128, causal=1).set_q_lens([4, 1, 0])
+    p = la.lean_attn_problem_schedule(ok, [100, 1, 50], tn)
+    # the schedule is that of the longest query for every sequence; a single query row still takes the MFMA kernel
+    assert (p.T_m, p.C_m, p.kernel) == (16, 1, 1)
+    assert bytes(p) == bytes(la.lean_attn_problem_schedule(_problem(3, 4, 8, 2, 128, causal=1), [100, 4, 50], tn))
+    assert la.lean_attn_problem_schedule(_problem(2, 1, 2, 2, 128).set_q_lens([1, 0]), [10, 10], tn).kernel == 1
+    assert status(_problem(3, 4, 8, 2, 128).set_q_lens([3, 1, 0]), [100, 1, 50]) == -2      # N_q is not the longest
+    assert status(_problem(3, 4, 8, 2, 128).set_q_lens([4, 5, 0]), [100, 9, 50]) == -2      # longer than N_q
+    assert status(_problem(3, 4, 8, 2, 128).set_q_lens([4, -1, 0]), [100, 9, 50]) == -2
+    assert status(_problem(3, 4, 8, 2, 128, causal=1).set_q_lens([4, 2, 0]), [100, 1, 50]) == -5   # 1 cached token, 2 queries
+    la.lean_attn_problem_schedule(_problem(3, 4, 8, 2, 128, causal=0).set_q_lens([4, 2, 0]), [100, 1, 50], tn)
+    assert ok.query_tokens() == 5 and _problem(3, 4, 8, 2, 128).query_tokens() == 12

@@ -36,6 +36,7 @@ class Workload:
     note: str = ""
     N_q: int = 1                    # query rows per sequence (the last N_q cached tokens)
     causal: bool = False            # query row i sees the first N_b - N_q + i + 1 cached tokens
+    q_lens: Optional[tuple] = None  # per-sequence query lengths (N_q is then the longest); q is packed
 
     @property
     def scale(self) -> float:
@@ -103,7 +104,7 @@ def scaled_down(w: Workload, factor: int, min_len: int = 1) -> Workload:
 @dataclass
 class Inputs:
     w: Workload
-    q: torch.Tensor                 # [B, Hq, D], or [B, N_q, Hq, D] when N_q > 1
+    q: torch.Tensor                 # [B, Hq, D]; [B, N_q, Hq, D] when N_q > 1; [sum(q_lens), Hq, D] when ragged
     k: torch.Tensor                 # PADDED [B, Hkv, n_stride, D] | PACKED [Hkv, total, D]
     v: torch.Tensor
     seqlens: List[int] = field(default_factory=list)
@@ -122,9 +123,13 @@ def generate(w: Workload, device="cpu", slab_rows: int = 1 << 16) -> Inputs:
     gen = torch.Generator(device=dev)
     gen.manual_seed(1000 + w.seed)
     dt = w.torch_dtype
-    q = torch.randn(w.B, w.N_q, w.Hq, w.D, generator=gen, device=dev, dtype=torch.float32).to(dt)
-    if w.N_q == 1:
-        q = q.view(w.B, w.Hq, w.D)
+    if w.q_lens is not None:
+        assert len(w.q_lens) == w.B and max(w.q_lens) == w.N_q
+        q = torch.randn(int(sum(w.q_lens)), w.Hq, w.D, generator=gen, device=dev, dtype=torch.float32).to(dt)
+    else:
+        q = torch.randn(w.B, w.N_q, w.Hq, w.D, generator=gen, device=dev, dtype=torch.float32).to(dt)
+        if w.N_q == 1:
+            q = q.view(w.B, w.Hq, w.D)
     if w.kv_layout == KV_PADDED:
         shape = (w.B * w.Hkv * w.n_stride, w.D)
         final = (w.B, w.Hkv, w.n_stride, w.D)
