@@ -197,8 +197,9 @@ __global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_d
     int parked_b = 0, parked_h = 0, parked_first = 0;
 
     int64_t it = cta_start;
+    Segment sg;
     while (it < cta_end) {
-        const Segment sg = locate(a.sched, a.table, it, cta_end);
+        sg = it == cta_start ? locate(a.sched, a.table, it, cta_end) : locate_next(a.sched, a.table, sg, g, cta_end);
         if (it == cta_start) stamp(a, g, 2);
         if (a.ragged_q && tile_rows(a, sg.b, sg.h).count <= 0) {
             // a sequence with fewer query tokens than the longest: this row block holds no rows.

@@ -129,6 +129,43 @@ LEAN_HD Segment locate(const Sched& s, const SchedTable& t, int64_t it, int64_t 
     return sg;
 }
 
+// The segment after `prev` in the span of CTA g (stream-K spans; prev.tile_iter_end < cta_end):
+// the next output tile in iteration order, from its first iteration, so this CTA is its host
+// block.  Same result as locate(s, t, prev.tile_iter_end, cta_end) without the searches and
+// divisions: the walk steps to the next head / next non-empty sequence.
+LEAN_HD Segment locate_next(const Sched& s, const SchedTable& t, const Segment& prev, int g, int64_t cta_end) {
+    Segment sg;
+    sg.b = prev.b;
+    sg.h = prev.h;
+    if (s.packed) {
+        do {
+            if (++sg.b == s.B) {
+                sg.b = 0;
+                ++sg.h;
+            }
+        } while (t.cu_iters[sg.b + 1] == t.cu_iters[sg.b]);
+        sg.tile_idx = sg.h * s.B + sg.b;
+    } else {
+        if (++sg.h == s.Hkv) {
+            sg.h = 0;
+            do ++sg.b; while (t.cu_iters[sg.b + 1] == t.cu_iters[sg.b]);
+        }
+        sg.tile_idx = sg.b * s.Hkv + sg.h;
+    }
+    const int32_t c_n = t.cu_iters[sg.b + 1] - t.cu_iters[sg.b];
+    const int64_t tile_iter = prev.tile_iter_end;
+    sg.n_ctx = t.cu_tok[sg.b + 1] - t.cu_tok[sg.b];
+    sg.tile_iter_end = tile_iter + c_n;
+    sg.local_iter = 0;
+    const int64_t stop = sg.tile_iter_end < cta_end ? sg.tile_iter_end : cta_end;
+    sg.local_iter_end = (int32_t)(stop - tile_iter);
+    sg.host = 1;
+    sg.finishing = cta_end >= sg.tile_iter_end;
+    sg.first_cta = g;
+    sg.last_cta = sg.finishing ? g : cta_of_iter(s, sg.tile_iter_end - 1);
+    return sg;
+}
+
 // The range of global iterations CTA g owns (empty when begin == end).
 LEAN_HD void span_of(const Sched& s, const SchedTable& t, int g, int64_t* begin, int64_t* end) {
     if (!s.fixed_split) {

@@ -317,3 +317,14 @@ def test_per_sequence_query_lengths_are_validated():
     assert status(_problem(3, 4, 8, 2, 128, causal=1).set_q_lens([4, 2, 0]), [100, 1, 50]) == -5   # 1 cached token, 2 queries
     la.lean_attn_problem_schedule(_problem(3, 4, 8, 2, 128, causal=0).set_q_lens([4, 2, 0]), [100, 1, 50], tn)
     assert ok.query_tokens() == 5 and _problem(3, 4, 8, 2, 128).query_tokens() == 12
+
+
+def test_many_short_contexts_put_two_workgroups_on_a_unit():
+    # large batches of short contexts: every span crosses several tile boundaries
+    assert _plan([1000] * 256, 32, 8, 128, la.BF16, la.KV_PADDED, num_cus=256).grid == 512
+    assert _plan([1500] * 64 + [0] * 8, 32, 8, 128, la.BF16, la.KV_PACKED, num_cus=256).grid == 512
+    # long contexts, or too few tiles to cross boundaries: one workgroup per unit
+    assert _plan([4000] * 256, 32, 8, 128, la.BF16, la.KV_PADDED, num_cus=256).grid == 256
+    assert _plan([1000] * 32, 32, 8, 128, la.BF16, la.KV_PADDED, num_cus=256).grid == 256
+    # an explicit request wins
+    assert _plan([1000] * 256, 32, 8, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=1).grid == 256
