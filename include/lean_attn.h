@@ -41,7 +41,7 @@ typedef enum lean_attn_status {
     LEAN_ATTN_ERR_WORKSPACE = -4,     /* workspace missing, misaligned or too small */
     LEAN_ATTN_ERR_SEQLEN = -5,        /* a negative length, N_b*D*2 >= 2^31 bytes, a padded stride below the longest,
                                          or (causal) 0 < N_b < N_q */
-    LEAN_ATTN_ERR_BATCH_TOO_LARGE = -6, /* B > LEAN_ATTN_MAX_BATCH */
+    LEAN_ATTN_ERR_BATCH_TOO_LARGE = -6, /* B > LEAN_ATTN_MAX_BATCH in a schedule query */
     LEAN_ATTN_ERR_HIP = -7,           /* a HIP runtime call failed (no device, bad stream, ...) */
     LEAN_ATTN_ERR_TUNING = -8,        /* a lean_attn_tuning field is out of range */
     LEAN_ATTN_ERR_PEER_TIMEOUT = -9   /* reported by lean_attn_workspace_status only */
@@ -64,7 +64,9 @@ typedef enum lean_attn_out_dtype { LEAN_ATTN_OUT_F32 = 0, LEAN_ATTN_OUT_AS_INPUT
  */
 typedef enum lean_attn_kv_layout { LEAN_ATTN_KV_PADDED = 0, LEAN_ATTN_KV_PACKED = 1 } lean_attn_kv_layout;
 
-#define LEAN_ATTN_MAX_BATCH 256  /* sequences per call (the schedule table travels as kernel arguments) */
+#define LEAN_ATTN_MAX_BATCH 256  /* sequences per launch (the schedule table travels as kernel arguments);
+                                    lean_attn_decode / lean_attn_attend split larger batches into
+                                    consecutive launches, the schedule queries describe one launch */
 #define LEAN_ATTN_MAX_TILE_ROWS 32    /* query rows of one output tile: two MFMA row blocks (one, 16 rows, at D = 256) */
 #define LEAN_ATTN_MAX_QUERY_ROWS 256  /* N_q * Hq / Hkv: query rows that share one KV head */
 #define LEAN_ATTN_MAX_GRID 4096  /* upper bound on workgroups; sizes the workspace */
@@ -220,7 +222,8 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
  *   scale    multiplies q.k before the softmax (1/sqrt(D) in Eq. 1)
  *   tuning   NULL for defaults
  * Supported: D in {64, 128, 256}, both dtypes, Hq/Hkv <= LEAN_ATTN_MAX_QUERY_ROWS,
- * B <= LEAN_ATTN_MAX_BATCH.  Same as lean_attn_attend with N_q = 1 and fp32 output.
+ * any B (batches beyond LEAN_ATTN_MAX_BATCH run as consecutive launches on the stream, sharing
+ * the workspace).  Same as lean_attn_attend with N_q = 1 and fp32 output.
  * q, k_cache, v_cache and out must be 16-byte aligned.
  * The first call per device and kernel variant reads the device's unit count and the
  * kernel's residency from the runtime (cached afterwards): make it outside graph capture.

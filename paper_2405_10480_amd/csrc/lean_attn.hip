@@ -147,19 +147,20 @@ static int query_device(int kernel, int dtype, int D, int shape, int T_m, int* c
     return LEAN_ATTN_OK;
 }
 
-static int check_problem(const lean_attn_problem& p) {
+// any_batch: the caller splits batches beyond LEAN_ATTN_MAX_BATCH itself (lean_attn_attend)
+static int check_problem(const lean_attn_problem& p, bool any_batch = false) {
     if (p.B <= 0 || p.N_q <= 0 || p.Hq <= 0 || p.Hkv <= 0 || p.Hq % p.Hkv != 0) return LEAN_ATTN_ERR_BAD_SHAPE;
     if ((int64_t)p.N_q * (p.Hq / p.Hkv) > LEAN_ATTN_MAX_QUERY_ROWS) return LEAN_ATTN_ERR_BAD_SHAPE;
     if (p.causal != 0 && p.causal != 1) return LEAN_ATTN_ERR_BAD_SHAPE;
     if (p.q_lens) {
         int longest = 0;
-        for (int b = 0; b < p.B && b < LEAN_ATTN_MAX_BATCH; ++b) {
+        for (int b = 0; b < p.B && (any_batch || b < LEAN_ATTN_MAX_BATCH); ++b) {
             if (p.q_lens[b] < 0 || p.q_lens[b] > p.N_q) return LEAN_ATTN_ERR_BAD_SHAPE;
             if (p.q_lens[b] > longest) longest = p.q_lens[b];
         }
         if (longest != p.N_q) return LEAN_ATTN_ERR_BAD_SHAPE;  // N_q is the longest query, by definition
     }
-    if (p.B > LEAN_ATTN_MAX_BATCH) return LEAN_ATTN_ERR_BATCH_TOO_LARGE;
+    if (p.B > LEAN_ATTN_MAX_BATCH && !any_batch) return LEAN_ATTN_ERR_BATCH_TOO_LARGE;
     if (dim_index(p.D) < 0) return LEAN_ATTN_ERR_UNSUPPORTED;
     if (p.dtype != LEAN_ATTN_F16 && p.dtype != LEAN_ATTN_BF16) return LEAN_ATTN_ERR_UNSUPPORTED;
     if (p.out_dtype != LEAN_ATTN_OUT_F32 && p.out_dtype != LEAN_ATTN_OUT_AS_INPUT) return LEAN_ATTN_ERR_UNSUPPORTED;
@@ -336,7 +337,7 @@ using namespace lean;
 extern "C" {
 
 size_t lean_attn_problem_workspace_size(const lean_attn_problem* problem) {
-    if (!problem || check_problem(*problem) != LEAN_ATTN_OK) return 0;
+    if (!problem || check_problem(*problem, true) != LEAN_ATTN_OK) return 0;  // the size does not depend on B
     return kPartialsOffset + (size_t)kMaxGrid * slot_floats(row_blocks(*problem).T_m, problem->D) * sizeof(float);
 }
 
@@ -435,31 +436,21 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
     return n;
 }
 
-int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void* k_cache, const void* v_cache,
-                     const int32_t* seqlens, void* out, float* lse, void* workspace, size_t workspace_bytes,
-                     const lean_attn_tuning* tuning, void* hip_stream) {
-    if (!problem || !q || !k_cache || !v_cache || !seqlens || !out || !workspace) return LEAN_ATTN_ERR_NULL_POINTER;
-    const lean_attn_problem& p = *problem;
-    int rc = check_problem(p);
-    if (rc != LEAN_ATTN_OK) return rc;
-    if ((((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15) != 0)
-        return LEAN_ATTN_ERR_BAD_SHAPE;
-    if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < lean_attn_problem_workspace_size(problem))
-        return LEAN_ATTN_ERR_WORKSPACE;
+// One launch: at most LEAN_ATTN_MAX_BATCH sequences.  `tok_base` / `tok_total`: position of this
+// batch's first token in a PACKED cache that holds `tok_total` tokens per head (0 and the batch's
+// own total when the batch is the whole cache).
+static int launch_one(const lean_attn_problem& p, const void* q, const void* k_cache, const void* v_cache,
+                      const int32_t* seqlens, void* out, float* lse, void* workspace, const lean_attn_tuning* tuning,
+                      hipStream_t stream, int64_t tok_base, int64_t tok_total) {
     const int B = p.B, D = p.D;
-
     lean_attn_plan plan;
     DecodeArgs a;
-    rc = make_schedule(p, seqlens, tuning, &plan, &a.sched, &a.table);
+    int rc = make_schedule(p, seqlens, tuning, &plan, &a.sched, &a.table);
     if (rc != LEAN_ATTN_OK) return rc;
-    int32_t longest = 0, has_empty = 0;
+    int32_t has_empty = 0;
     for (int b = 0; b < B; ++b) {
-        if (seqlens[b] > longest) longest = seqlens[b];
         if (seqlens[b] == 0) has_empty = 1;
     }
-    if (p.kv_layout == LEAN_ATTN_KV_PADDED && p.kv_seq_stride < longest) return LEAN_ATTN_ERR_SEQLEN;
-
-    hipStream_t stream = (hipStream_t)hip_stream;
     const int out16 = p.out_dtype == LEAN_ATTN_OUT_AS_INPUT;
     if (plan.total_iters == 0) {  // every sequence is empty
         const int64_t rows = (int64_t)a.table.cu_q[B] * p.Hq;
@@ -484,7 +475,10 @@ int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void
     a.flags = (uint32_t*)((char*)workspace + kFlagsOffset);
     a.partials = (float*)((char*)workspace + kPartialsOffset);
     a.kv_seq_stride = p.kv_seq_stride;
-    a.total_rows = a.table.cu_tok[B];
+    if (tok_base != 0) {
+        for (int b = 0; b <= B; ++b) a.table.cu_tok[b] += (int32_t)tok_base;
+    }
+    a.total_rows = tok_total;
     a.Hq = p.Hq;
     a.Hkv = p.Hkv;
     a.N_q = p.N_q;
@@ -508,6 +502,71 @@ int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void
     if (hipLaunchKernel(var.fn, dim3(plan.grid), dim3(var.threads), params, 0, stream) != hipSuccess) {
         (void)hipGetLastError();
         return LEAN_ATTN_ERR_HIP;
+    }
+    return LEAN_ATTN_OK;
+}
+
+int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void* k_cache, const void* v_cache,
+                     const int32_t* seqlens, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                     const lean_attn_tuning* tuning, void* hip_stream) {
+    if (!problem || !q || !k_cache || !v_cache || !seqlens || !out || !workspace) return LEAN_ATTN_ERR_NULL_POINTER;
+    const lean_attn_problem& p = *problem;
+    int rc = check_problem(p, true);
+    if (rc != LEAN_ATTN_OK) return rc;
+    if ((((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15) != 0)
+        return LEAN_ATTN_ERR_BAD_SHAPE;
+    if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < lean_attn_problem_workspace_size(problem))
+        return LEAN_ATTN_ERR_WORKSPACE;
+    // every length is checked before the first launch: on error nothing runs
+    int64_t tok_total = 0;
+    for (int b = 0; b < p.B; ++b) {
+        const int64_t n = seqlens[b];
+        const int q_len = p.q_lens ? p.q_lens[b] : p.N_q;
+        if (n < 0 || n * p.D * 2 > INT32_MAX) return LEAN_ATTN_ERR_SEQLEN;
+        if (p.causal && n != 0 && n < q_len) return LEAN_ATTN_ERR_SEQLEN;
+        if (p.kv_layout == LEAN_ATTN_KV_PADDED && p.kv_seq_stride < n) return LEAN_ATTN_ERR_SEQLEN;
+        tok_total += n;
+        if (tok_total > INT32_MAX) return LEAN_ATTN_ERR_SEQLEN;
+    }
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (p.B <= LEAN_ATTN_MAX_BATCH)
+        return launch_one(p, q, k_cache, v_cache, seqlens, out, lse, workspace, tuning, stream, 0, tok_total);
+
+    // A larger batch: consecutive launches of at most LEAN_ATTN_MAX_BATCH sequences on the same
+    // stream (the schedule table of one launch travels in its kernel arguments) sharing the workspace.
+    const size_t out_elem = p.out_dtype == LEAN_ATTN_OUT_AS_INPUT ? 2 : 4;
+    int64_t tok_base = 0, row_base = 0;  // tokens / (query token, head) rows before the chunk
+    for (int b0 = 0; b0 < p.B; b0 += LEAN_ATTN_MAX_BATCH) {
+        lean_attn_problem c = p;
+        c.B = p.B - b0 < LEAN_ATTN_MAX_BATCH ? p.B - b0 : LEAN_ATTN_MAX_BATCH;
+        int64_t chunk_toks = 0, chunk_q = 0;
+        int longest_q = 0;
+        for (int b = 0; b < c.B; ++b) {
+            chunk_toks += seqlens[b0 + b];
+            const int q_len = p.q_lens ? p.q_lens[b0 + b] : p.N_q;
+            chunk_q += q_len;
+            if (q_len > longest_q) longest_q = q_len;
+        }
+        if (longest_q > 0) {  // (a chunk without any query token has nothing to compute)
+            if (p.q_lens) {
+                c.q_lens = p.q_lens + b0;
+                c.N_q = longest_q;
+            }
+            const char* kc = (const char*)k_cache;
+            const char* vc = (const char*)v_cache;
+            if (p.kv_layout == LEAN_ATTN_KV_PADDED) {
+                const size_t skip = (size_t)b0 * p.Hkv * (size_t)p.kv_seq_stride * p.D * 2;
+                kc += skip;
+                vc += skip;
+            }
+            rc = launch_one(c, (const char*)q + (size_t)row_base * p.D * 2, kc, vc, seqlens + b0,
+                            (char*)out + (size_t)row_base * p.D * out_elem, lse ? lse + row_base : nullptr, workspace,
+                            tuning, stream, p.kv_layout == LEAN_ATTN_KV_PACKED ? tok_base : 0,
+                            p.kv_layout == LEAN_ATTN_KV_PACKED ? tok_total : chunk_toks);
+            if (rc != LEAN_ATTN_OK) return rc;
+        }
+        tok_base += chunk_toks;
+        row_base += chunk_q * p.Hq;
     }
     return LEAN_ATTN_OK;
 }

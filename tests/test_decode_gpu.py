@@ -295,6 +295,40 @@ def test_maximum_batch_ragged():
     assert e.value.status == la.binding.ERR_BATCH_TOO_LARGE
 
 
+def test_batches_beyond_one_launch_are_split():
+    # 700 sequences: three consecutive launches share the workspace; decode, both layouts
+    r = np.random.default_rng(700)
+    seqlens = [int(x) for x in r.integers(0, 300, size=700)]
+    seqlens[255], seqlens[256], seqlens[511], seqlens[512] = 299, 0, 1, 257
+    for group, layout in ((1, workloads.KV_PACKED), (4, workloads.KV_PADDED)):
+        inp = _mk(len(seqlens), 2 * group, 2, 64, "bf16", seqlens, layout, seed=34)
+        want, want_lse = _oracle(inp)
+        got, got_lse, _ = _run(inp)
+        _check(got, got_lse, want, want_lse, f"B=700 group={group}")
+    # per-sequence query lengths across the launch boundaries, one chunk without any query token
+    q_lens = [int(x) for x in r.integers(0, 4, size=700)]
+    q_lens[256:512] = [0] * 256
+    q_lens[0], q_lens[699] = 3, 2
+    seq2 = [max(n, q) for n, q in zip(seqlens, q_lens)]
+    w = workloads.Workload("b700_mixed", 700, 8, 2, 128, "f16", tuple(seq2), workloads.KV_PACKED, seed=35,
+                           N_q=max(q_lens), causal=True, q_lens=tuple(q_lens))
+    inp = workloads.generate(w, device="cuda")
+    want, want_lse = _oracle_ragged(inp)
+    got, got_lse = _run_ragged(inp)
+    _check(got.cpu().numpy(), got_lse, want, want_lse, "B=700 mixed")
+    # an invalid length in the last chunk: nothing may have been launched
+    bad = list(seqlens)
+    bad[650] = -1
+    out = torch.full((700, 2, 64), 7.0, dtype=torch.float32, device="cuda")
+    inp = _mk(700, 2, 2, 64, "bf16", seqlens, workloads.KV_PADDED, seed=34)
+    ws = _workspace(700, 2, 2, 64, la.BF16)
+    with pytest.raises(la.LeanAttnError) as e:
+        la.lean_attn_decode(inp.q, inp.k, inp.v, bad, out, ws, Hkv=2, kv_layout=la.KV_PADDED,
+                            kv_seq_stride=inp.w.n_stride, scale=0.125)
+    torch.cuda.synchronize()
+    assert e.value.status == la.binding.ERR_SEQLEN and torch.all(out == 7.0)
+
+
 # ------------------------------------------------------------------ the five workloads, scaled down
 @pytest.mark.parametrize("idx,factor", [(1, 1), (2, 8), (3, 16), (4, 16), (5, 16)])
 def test_named_workloads_scaled(idx, factor):
