@@ -110,7 +110,8 @@ typedef struct lean_attn_tuning {
     int32_t kernel;        /* 0 default, 1 force VALU kernel (needs N_q * Hq == Hkv), 2 force MFMA kernel */
     int32_t xcd_remap;     /* 0 default, 1 off, 2 on: place consecutive spans on one XCD */
     int32_t spin_limit;    /* polls before a waiting CTA gives up and reports PEER_TIMEOUT */
-    int32_t merge_fanin;   /* partials a CTA merges per level of the reduction tree; 0 default (8),
+    int32_t merge_fanin;   /* partials a CTA merges per level of the reduction tree; 0 default (8; 32 for
+                              single-row tiles, which merge a level as wide as the workgroup),
                               >= LEAN_ATTN_MAX_GRID gives Algorithm 2's flat list: the host block
                               merges every peer itself */
     int32_t tile_shape;    /* 0 default; 1..5 other compiled (loads per lane, waves per workgroup)

@@ -32,6 +32,7 @@ static_assert(kMaxGrid == LEAN_ATTN_MAX_GRID, "header and workspace layout disag
 constexpr int kDefaultCtasPerCu = 1;
 constexpr int kShortContextTokens = 1536;  // mean context at or below which two workgroups share a unit
 constexpr int kDefaultFanin = 8;
+constexpr int kDefaultFaninSingleRow = 32;
 constexpr int kDefaultGridMultiple = 1;
 constexpr int kMaxProbeMode = 5;
 constexpr int kNumShapes = 6;
@@ -494,7 +495,9 @@ static int launch_one(const lean_attn_problem& p, const void* q, const void* k_c
     a.xcd_remap = (tuning && tuning->xcd_remap == 2 && plan.grid <= plan.max_resident) ? 1 : 0;
     a.spin_limit = (tuning && tuning->spin_limit > 0) ? tuning->spin_limit : (1 << 22);
     a.has_empty = has_empty;
-    a.fanin = (tuning && tuning->merge_fanin >= 2) ? tuning->merge_fanin : kDefaultFanin;
+    // single-row tiles merge a whole level of up to 32 partials in one round trip (see merge_children_wide)
+    a.fanin = (tuning && tuning->merge_fanin >= 2) ? tuning->merge_fanin
+                                                   : (plan.kernel == 0 ? kDefaultFaninSingleRow : kDefaultFanin);
     a.cta_clock = tuning ? (unsigned long long*)tuning->cta_clock : nullptr;
     a.scale_log2e = p.scale * 1.4426950408889634f;
 

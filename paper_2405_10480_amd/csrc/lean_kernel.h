@@ -57,6 +57,74 @@ __device__ __forceinline__ void merge_children(const DecodeArgs& a, OwnPartial<C
     }
 }
 
+// The same for single-row tiles (T_m = 1: D/4 chunks, far fewer than threads), as wide as the
+// workgroup: thread (slot, chunk) merges children slot, slot + SLOTS, ... of its chunk, four
+// loads in flight each, the SLOTS partial results meet in LDS and the owners of `own` fold
+// them in slot order.  Up to 4*SLOTS children cost one memory round trip instead of one per
+// seven, which lets small problems reduce in a single tree level.  The order is fixed, so the
+// result stays reproducible bit for bit.
+template <int THREADS>
+struct WideMergeScratch {
+    f32x4 o[THREADS];
+    float m[THREADS];
+    float l[THREADS];
+};
+
+template <int THREADS, int D>
+__device__ __forceinline__ void merge_children_wide(const DecodeArgs& a, OwnPartial<1>& own, int first, int step,
+                                                    int nchild, WideMergeScratch<THREADS>& sh) {
+    constexpr int NCH = D / 4;
+    constexpr int SLOTS = THREADS / NCH;
+    static_assert(SLOTS >= 2 && SLOTS * NCH == THREADS, "single-row tiles are much smaller than the workgroup");
+    const int tid = threadIdx.x;
+    const int slot = tid / NCH, c = tid % NCH;
+    const buffer_rsrc ws = make_slab((const uint16_t*)a.partials, (uint32_t)a.sched.grid * (uint32_t)a.slot * 4u);
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY, l = 0.f;
+    for (int j0 = slot; j0 < nchild; j0 += 4 * SLOTS) {
+        f32x4 oc[4];
+        float mc[4], lc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int j = j0 + u * SLOTS;
+            const int jj = j < nchild ? j : j0;  // past the last child: re-read a valid one, weight it zero
+            const uint32_t base = (uint32_t)(first + jj * step) * (uint32_t)a.slot * 4u;
+            oc[u] = partial_load16(ws, base + 16u * c);
+            mc[u] = partial_load4(ws, base + 4u * D);
+            lc[u] = partial_load4(ws, base + 4u * (D + 1));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float m_cta = j0 + u * SLOTS < nchild ? mc[u] : -INFINITY;
+            const float m_new = fmaxf(m_cta, m);
+            const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+            const float w_cta = fast_exp2(m_cta - m_ref);
+            const float w_acc = fast_exp2(m - m_ref);
+            l = w_cta * lc[u] + w_acc * l;
+            o = w_cta * oc[u] + w_acc * o;
+            m = m_new;
+        }
+    }
+    sh.o[tid] = o;
+    sh.m[tid] = m;
+    sh.l[tid] = l;
+    __syncthreads();
+    if (tid < NCH) {
+#pragma unroll
+        for (int sl = 0; sl < SLOTS; ++sl) {
+            const float m_s = sh.m[sl * NCH + tid];
+            const float m_new = fmaxf(m_s, own.m[0]);
+            const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+            const float w_s = fast_exp2(m_s - m_ref);
+            const float w_own = fast_exp2(own.m[0] - m_ref);
+            own.l[0] = w_s * sh.l[sl * NCH + tid] + w_own * own.l[0];
+            own.o[0] = w_s * sh.o[sl * NCH + tid] + w_own * own.o[0];
+            own.m[0] = m_new;
+        }
+    }
+    __syncthreads();  // the scratch is reused by the next batch
+}
+
 // Reduction of one output tile across the CTAs that computed parts of it, then either the
 // publication of this CTA's (merged) partial or the final write.
 //
@@ -70,7 +138,7 @@ __device__ __forceinline__ void merge_children(const DecodeArgs& a, OwnPartial<C
 // ends even when the grid is larger than what is resident at once.
 template <class Core, int CPT, int F>
 __device__ __forceinline__ void reduce_tile(const DecodeArgs& a, OwnPartial<CPT>& own, int g, int b, int h,
-                                            int first_cta, int last_cta) {
+                                            int first_cta, int last_cta, void* wide_scratch) {
     constexpr int D = Core::kD;
     constexpr int THREADS = Core::kThreads;
     const int tid = threadIdx.x;
@@ -88,12 +156,25 @@ __device__ __forceinline__ void reduce_tile(const DecodeArgs& a, OwnPartial<CPT>
         int remaining = (int)((nranks - 1 - rank) / stride);  // children at this level
         if (remaining > a.fanin - 1) remaining = a.fanin - 1;
         int child = g - (int)stride;
-        while (remaining > 0) {  // batches of at most F-1 partials
-            const int batch = remaining < F - 1 ? remaining : F - 1;
-            wait_arrivals(a.flags, child, -(int)stride, batch, a.status, a.spin_limit);
-            merge_children<CPT, THREADS, D, F>(a, own, child, -(int)stride, batch, n_chunks, n_elem, T_m);
-            child -= batch * (int)stride;
-            remaining -= batch;
+        if constexpr (Core::kTmMax == 1) {
+            // single-row tiles: batches as wide as four children per slot of the workgroup
+            constexpr int kWide = 4 * (THREADS / (D / 4));
+            while (remaining > 0) {
+                const int batch = remaining < kWide ? remaining : kWide;
+                wait_arrivals(a.flags, child, -(int)stride, batch, a.status, a.spin_limit);
+                merge_children_wide<THREADS, D>(a, own, child, -(int)stride, batch,
+                                                *static_cast<WideMergeScratch<THREADS>*>(wide_scratch));
+                child -= batch * (int)stride;
+                remaining -= batch;
+            }
+        } else {
+            while (remaining > 0) {  // batches of at most F-1 partials
+                const int batch = remaining < F - 1 ? remaining : F - 1;
+                wait_arrivals(a.flags, child, -(int)stride, batch, a.status, a.spin_limit);
+                merge_children<CPT, THREADS, D, F>(a, own, child, -(int)stride, batch, n_chunks, n_elem, T_m);
+                child -= batch * (int)stride;
+                remaining -= batch;
+            }
         }
     }
     if (publish) {
@@ -149,6 +230,11 @@ __global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_d
     __shared__ f32x4 parked_o[CPT * THREADS];
     __shared__ float parked_m[CPT * THREADS];
     __shared__ float parked_l[CPT * THREADS];
+    void* wide_scratch = nullptr;
+    if constexpr (Core::kTmMax == 1) {
+        __shared__ WideMergeScratch<THREADS> wide;
+        wide_scratch = &wide;
+    }
 
     // Read every scalar argument now, in one batch: left to itself the compiler loads each field
     // right before its first use, and the span walk below becomes a chain of dependent round
@@ -247,7 +333,7 @@ __global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_d
             parked_h = sg.h;
             parked_first = sg.first_cta;
         } else {
-            reduce_tile<Core, CPT, F>(a, own, g, sg.b, sg.h, sg.first_cta, sg.last_cta);
+            reduce_tile<Core, CPT, F>(a, own, g, sg.b, sg.h, sg.first_cta, sg.last_cta, wide_scratch);
         }
         it = sg.tile_iter_end;
         __syncthreads();  // the cores reuse the shared partial streams
@@ -261,7 +347,7 @@ __global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_d
             own.m[i] = parked_m[tid + i * THREADS];
             own.l[i] = parked_l[tid + i * THREADS];
         }
-        reduce_tile<Core, CPT, F>(a, own, g, parked_b, parked_h, parked_first, g);
+        reduce_tile<Core, CPT, F>(a, own, g, parked_b, parked_h, parked_first, g, wide_scratch);
     }
     stamp(a, g, 3);
 }
