@@ -258,8 +258,9 @@ int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void
  * stream-K spans); mode 1: the workgroups sweep the buffer together in 32 KiB
  * chunks dealt round-robin; modes 2, 3, 4: as mode 0 through a buffer descriptor
  * with cache policy nt, sc1, sc0|sc1 on the loads; mode 5: non-temporal 16-byte pieces
- * strided over 16 rows of 256 bytes per wave-wide load (the K operand pattern of the
- * MFMA core).  Used to report the streaming-read ceiling of the
+ * strided over 16 rows of 256 bytes per wave-wide load (the operand pattern the MFMA
+ * core avoids by staging K through LDS); mode 6: non-temporal half rows (256 bytes) of four
+ * consecutive 512-byte rows per wave-wide load (the K/V pattern of the MFMA core at D = 256).  Used to report the streaming-read ceiling of the
  * machine next to the decode rate.  `sink` is a device pointer to at least
  * 4 bytes.  bytes must be a multiple of 16.
  */

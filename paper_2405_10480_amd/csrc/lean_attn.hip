@@ -34,7 +34,7 @@ constexpr int kShortContextTokens = 1536;  // mean context at or below which two
 constexpr int kDefaultFanin = 8;
 constexpr int kDefaultFaninSingleRow = 32;
 constexpr int kDefaultGridMultiple = 1;
-constexpr int kMaxProbeMode = 5;
+constexpr int kMaxProbeMode = 6;
 constexpr int kNumShapes = 6;
 
 struct Variant {

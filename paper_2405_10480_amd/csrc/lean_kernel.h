@@ -406,6 +406,28 @@ __device__ __forceinline__ uint32_t probe_rowstrided(const uint4* buf, int64_t l
     return acc;
 }
 
+// mode 6: the K/V access pattern of the MFMA core at D = 256: per wave-wide load, lane (r, g)
+// reads 16 bytes at byte 16*r of one half (256 bytes) of row g of a 4-row group; the two halves
+// of the rows come from consecutive load instructions (non-temporal).
+__device__ __forceinline__ uint32_t probe_halfrows(const uint4* buf, int64_t lo, int64_t hi) {
+    uint32_t acc = 0;
+    const int64_t span = hi - lo;
+    const buffer_rsrc r = make_slab((const uint16_t*)(buf + lo), (uint32_t)(span * 16));
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const uint32_t lane_off = (uint32_t)(lane >> 4) * 512u + (uint32_t)(lane & 15) * 16u;
+    // a workgroup step = 4 waves x 16 rows x 512 B = 32 KiB
+    for (int64_t i = 0; (i + 1) * 2048 <= span; ++i) {
+        const uint32_t base = (uint32_t)(i * 32768) + (uint32_t)w * 8192u + lane_off;
+        u32x4 x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            x[u] = __builtin_amdgcn_raw_buffer_load_b128(r, (int)(base + (u >> 1) * 2048u + (u & 1) * 256u), 0, 2);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
+    }
+    return acc;
+}
+
 __global__ __launch_bounds__(256) void lean_read_probe_kernel(const uint4* buf, int64_t n_vec, uint32_t* sink,
                                                               int mode) {
     const int G = gridDim.x;
@@ -424,7 +446,8 @@ __global__ __launch_bounds__(256) void lean_read_probe_kernel(const uint4* buf, 
     if (mode >= 2) {
         if (lo < hi)
             acc = mode == 2 ? probe_slab<2>(buf, lo, hi) : mode == 3 ? probe_slab<16>(buf, lo, hi)
-                  : mode == 4 ? probe_slab<17>(buf, lo, hi) : probe_rowstrided(buf, lo, hi);
+                  : mode == 4 ? probe_slab<17>(buf, lo, hi)
+                  : mode == 5 ? probe_rowstrided(buf, lo, hi) : probe_halfrows(buf, lo, hi);
     } else {
         int64_t i = lo + threadIdx.x;
         for (; i + 7 * 256 < hi; i += step) {

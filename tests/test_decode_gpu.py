@@ -602,3 +602,22 @@ def test_mixed_batch_long_contexts_and_sixteen_bit_output():
     inp_r = workloads.Inputs(wr, inp_u.q.reshape(6, 8, 128), inp_u.k, inp_u.v, list(wr.seqlens))
     b, b_lse = _run_ragged(inp_r)
     assert torch.equal(a.reshape(6, 8, 128), b) and np.array_equal(a_lse.reshape(6, 8), b_lse)
+
+
+def test_read_probe_modes_and_argument_checks():
+    # the measurement helper: every access pattern runs on ragged sizes, bad arguments are refused
+    sink = torch.zeros(16, dtype=torch.int32, device="cuda")
+    for nbytes in (16, 4096 + 16, (3 << 20) + 48):
+        buf = torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device="cuda")
+        for mode in range(7):
+            for grid in (1, 7, 512):
+                la.lean_attn_read_probe(buf, sink, grid, mode)
+    torch.cuda.synchronize()
+    assert int(sink[0].item()) in (0, 0x9e3779b9 - (1 << 32))     # only written if the folded word hits one magic value
+    buf = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    for kwargs in (dict(grid=0, mode=0), dict(grid=70000, mode=0), dict(grid=4, mode=7), dict(grid=4, mode=-1)):
+        with pytest.raises(la.LeanAttnError) as e:
+            la.lean_attn_read_probe(buf, sink, **kwargs)
+        assert e.value.status == la.binding.ERR_BAD_SHAPE
+    with pytest.raises(la.LeanAttnError):
+        la.lean_attn_read_probe(buf[:40], sink, 4, 0)            # not a multiple of 16 bytes
