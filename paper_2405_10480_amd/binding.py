@@ -194,10 +194,29 @@ def lean_attn_walk(plan: Plan, seqlens, Hkv, kv_layout, g, max_segments: int = 4
     return [dict(zip(keys, (int(buf[8 * i + j]) for j in range(8)))) for i in range(n)]
 
 
+class PreparedCall:
+    """One ``lean_attn_decode`` / ``lean_attn_attend`` call with its arguments checked and marshalled
+    once: calling the object only crosses the C ABI (for loops that launch on the same buffers
+    again and again, where the per-call checks above would cost more host time than the launch).
+    It keeps the tensors and host arrays it points to alive; the stream is the one given (or
+    current) at preparation."""
+    __slots__ = ("_fn", "_args", "_keep")
+
+    def __init__(self, fn, args, keep):
+        self._fn, self._args, self._keep = fn, args, keep
+
+    def __call__(self) -> None:
+        rc = self._fn(*self._args)
+        if rc != OK:
+            raise LeanAttnError(rc)
+
+
 def lean_attn_decode(q, k_cache, v_cache, seqlens, out, workspace, *, Hkv: int, kv_layout: int = KV_PADDED,
                      kv_seq_stride: int = 0, scale: float, lse=None, tuning: Optional[Tuning] = None,
-                     stream=None) -> None:
-    """Launch decode attention on the current (or given) HIP stream.  Shapes as in ``lean_attn.h``."""
+                     stream=None, prepare_only: bool = False):
+    """Launch decode attention on the current (or given) HIP stream.  Shapes as in ``lean_attn.h``.
+
+    With ``prepare_only`` nothing is launched and a :class:`PreparedCall` is returned instead."""
     B, Hq, D = q.shape
     if not (q.is_cuda and k_cache.is_cuda and v_cache.is_cuda and out.is_cuda and workspace.is_cuda):
         raise ValueError("q, k_cache, v_cache, out and workspace must be device tensors")
@@ -218,11 +237,13 @@ def lean_attn_decode(q, k_cache, v_cache, seqlens, out, workspace, *, Hkv: int, 
     if lse is not None and (str(lse.dtype) != "torch.float32" or lse.numel() != B * Hq or not lse.is_cuda):
         raise ValueError("lse must be a float32 device tensor [B, Hq]")
     arr = _seqlens_array(seqlens)
-    rc = _load().lean_attn_decode(
-        q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), arr, out.data_ptr(),
-        lse.data_ptr() if lse is not None else None, workspace.data_ptr(),
-        workspace.numel() * workspace.element_size(), B, Hq, Hkv, D, kv_layout, int(kv_seq_stride),
-        float(scale), _dtype_code(q), _tuning_ptr(tuning), _stream_handle(stream))
+    args = (q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), arr, out.data_ptr(),
+            lse.data_ptr() if lse is not None else None, workspace.data_ptr(),
+            workspace.numel() * workspace.element_size(), B, Hq, Hkv, D, kv_layout, int(kv_seq_stride),
+            float(scale), _dtype_code(q), _tuning_ptr(tuning), _stream_handle(stream))
+    if prepare_only:
+        return PreparedCall(_load().lean_attn_decode, args, (q, k_cache, v_cache, out, lse, workspace, arr, tuning))
+    rc = _load().lean_attn_decode(*args)
     if rc != OK:
         raise LeanAttnError(rc)
 
@@ -243,8 +264,10 @@ def lean_attn_problem_schedule(problem: Problem, seqlens, tuning: Optional[Tunin
 
 
 def lean_attn_attend(problem: Problem, q, k_cache, v_cache, seqlens, out, workspace, *, lse=None,
-                     tuning: Optional[Tuning] = None, stream=None) -> None:
-    """Launch attention of ``problem.N_q`` query rows per sequence.  Shapes as in ``lean_attn.h``."""
+                     tuning: Optional[Tuning] = None, stream=None, prepare_only: bool = False):
+    """Launch attention of ``problem.N_q`` query rows per sequence.  Shapes as in ``lean_attn.h``.
+
+    With ``prepare_only`` nothing is launched and a :class:`PreparedCall` is returned instead."""
     p = problem
     if not (q.is_cuda and k_cache.is_cuda and v_cache.is_cuda and out.is_cuda and workspace.is_cuda):
         raise ValueError("q, k_cache, v_cache, out and workspace must be device tensors")
@@ -270,10 +293,13 @@ def lean_attn_attend(problem: Problem, q, k_cache, v_cache, seqlens, out, worksp
         raise ValueError("PACKED k_cache must be [Hkv, sum(seqlens), D]")
     if lse is not None and (str(lse.dtype) != "torch.float32" or lse.numel() != n_rows or not lse.is_cuda):
         raise ValueError("lse must be a float32 device tensor [B, N_q, Hq] (or [sum(q_lens), Hq])")
-    rc = _load().lean_attn_attend(
-        ctypes.byref(p), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), _seqlens_array(seqlens),
-        out.data_ptr(), lse.data_ptr() if lse is not None else None, workspace.data_ptr(),
-        workspace.numel() * workspace.element_size(), _tuning_ptr(tuning), _stream_handle(stream))
+    arr = _seqlens_array(seqlens)
+    args = (ctypes.byref(p), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), arr,
+            out.data_ptr(), lse.data_ptr() if lse is not None else None, workspace.data_ptr(),
+            workspace.numel() * workspace.element_size(), _tuning_ptr(tuning), _stream_handle(stream))
+    if prepare_only:
+        return PreparedCall(_load().lean_attn_attend, args, (p, q, k_cache, v_cache, out, lse, workspace, arr, tuning))
+    rc = _load().lean_attn_attend(*args)
     if rc != OK:
         raise LeanAttnError(rc)
 

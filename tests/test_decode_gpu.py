@@ -621,3 +621,34 @@ def test_read_probe_modes_and_argument_checks():
         assert e.value.status == la.binding.ERR_BAD_SHAPE
     with pytest.raises(la.LeanAttnError):
         la.lean_attn_read_probe(buf[:40], sink, 4, 0)            # not a multiple of 16 bytes
+
+
+def test_prepared_call_replays_the_checked_call():
+    inp = _mk(2, 8, 2, 128, "bf16", [7000, 333], workloads.KV_PADDED, seed=97)
+    w = inp.w
+    ws = _workspace(w.B, w.Hq, w.Hkv, w.D, la.BF16)
+    direct = torch.empty(w.B, w.Hq, w.D, dtype=torch.float32, device="cuda")
+    la.lean_attn_decode(inp.q, inp.k, inp.v, inp.seqlens, direct, ws, Hkv=w.Hkv, kv_seq_stride=w.n_stride, scale=w.scale)
+    out = torch.full_like(direct, float("nan"))
+    call = la.lean_attn_decode(inp.q, inp.k, inp.v, inp.seqlens, out, ws, Hkv=w.Hkv, kv_seq_stride=w.n_stride,
+                               scale=w.scale, prepare_only=True)
+    torch.cuda.synchronize()
+    assert isinstance(call, la.PreparedCall) and torch.all(torch.isnan(out))      # nothing launched yet
+    for _ in range(3):
+        out.fill_(float("nan"))
+        call()
+        torch.cuda.synchronize()
+        assert torch.equal(out, direct)
+    # the general entry point, and a prepared call that the library refuses when it is made
+    inp2 = _mk_tile(2, 3, 8, 2, 128, "bf16", [500, 40], workloads.KV_PADDED, seed=96, causal=True)
+    a, _ = _run_attend(inp2)
+    pr = _problem_of(inp2.w)
+    ws2 = torch.empty(la.lean_attn_problem_workspace_size(pr), dtype=torch.uint8, device="cuda")
+    la.lean_attn_workspace_init(ws2)
+    b = torch.empty_like(a)
+    la.lean_attn_attend(pr, inp2.q, inp2.k, inp2.v, inp2.seqlens, b, ws2, prepare_only=True)()
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    bad = la.lean_attn_attend(pr, inp2.q, inp2.k, inp2.v, [500, 2], b, ws2, prepare_only=True)   # 2 < N_q, causal
+    with pytest.raises(la.LeanAttnError):
+        bad()
