@@ -652,3 +652,60 @@ def test_prepared_call_replays_the_checked_call():
     bad = la.lean_attn_attend(pr, inp2.q, inp2.k, inp2.v, [500, 2], b, ws2, prepare_only=True)   # 2 < N_q, causal
     with pytest.raises(la.LeanAttnError):
         bad()
+
+
+def test_seeded_random_problems_against_the_oracle():
+    # 60 seeded problems over every option at once: shapes, layouts, masks, per-sequence query
+    # lengths, output type, schedule overrides
+    r = np.random.default_rng(20240517)
+    for case in range(60):
+        D = int(r.choice([64, 128, 256]))
+        Hkv = int(r.integers(1, 4))
+        group = int(r.choice([1, 2, 3, 4, 7, 8, 16, 20]))
+        N_q = int(r.choice([1, 1, 2, 3, 5, 8]))
+        if N_q * group > 256:
+            N_q = 1
+        B = int(r.integers(1, 6))
+        causal = bool(r.integers(0, 2)) and N_q > 1
+        ragged_q = bool(r.integers(0, 2)) and N_q > 1
+        q_lens = [int(x) for x in r.integers(0, N_q + 1, size=B)] if ragged_q else [N_q] * B
+        if ragged_q:
+            q_lens[int(r.integers(0, B))] = N_q
+        seqlens = []
+        for b in range(B):
+            kind = int(r.integers(0, 6))
+            n = [0, q_lens[b], int(r.integers(1, 70)), int(r.integers(70, 700)), int(r.integers(700, 5000)),
+                 64 * int(r.integers(1, 20))][kind]
+            if causal and n != 0:
+                n = max(n, q_lens[b])
+            seqlens.append(n)
+        layout = int(r.integers(0, 2))
+        dtype = "bf16" if r.integers(0, 2) else "f16"
+        out_dtype = la.OUT_AS_INPUT if r.integers(0, 3) == 0 else la.OUT_F32
+        tn = la.Tuning(grid=int(r.choice([0, 0, 1, 5, 64, 700])), merge_fanin=int(r.choice([0, 0, 2, 5, 4096])),
+                       tile_shape=int(r.integers(0, 6)), ctas_per_cu=int(r.choice([0, 1, 2])),
+                       fixed_split=int(r.choice([0, 0, 0, 1, 3])))
+        label = (f"case {case}: D={D} Hkv={Hkv} g={group} N_q={N_q} q_lens={q_lens if ragged_q else None} B={B} "
+                 f"seqlens={seqlens} causal={causal} layout={layout} {dtype} out16={out_dtype} grid={tn.grid} "
+                 f"fanin={tn.merge_fanin} shape={tn.tile_shape} per_cu={tn.ctas_per_cu} split={tn.fixed_split}")
+        w = workloads.Workload(f"rnd{case}", B, Hkv * group, Hkv, D, dtype, tuple(seqlens), layout, seed=3000 + case,
+                               outlier_frac=0.02 if case % 3 == 0 else 0.0, N_q=N_q, causal=causal,
+                               q_lens=tuple(q_lens) if ragged_q else None)
+        if layout == workloads.KV_PADDED and max(seqlens) == 0:
+            continue                                  # a padded cache of stride 0 has no memory to point at
+        inp = workloads.generate(w, device="cuda")
+        if ragged_q:
+            if sum(q_lens) == 0:
+                continue
+            want, want_lse = _oracle_ragged(inp)
+            got, got_lse = _run_ragged(inp, tn, out_dtype)
+        else:
+            want, want_lse = _oracle_attend(inp)
+            got, got_lse = _run_attend(inp, tn, out_dtype)
+        got = got.float().cpu().numpy().reshape(want.shape)
+        got_lse = got_lse.reshape(want_lse.shape)
+        if out_dtype == la.OUT_F32:
+            _check(got, got_lse, want, want_lse, label)
+        else:
+            half_ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -11
+            assert np.all(np.abs(got - want) <= TIGHT_ABS + half_ulp * np.abs(want) * 1.01 + 1e-7), label
