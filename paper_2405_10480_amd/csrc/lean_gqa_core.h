@@ -96,6 +96,10 @@ struct GqaCore {
     static constexpr int kCH = NBLK * 16;       // tokens per wave per step
     static constexpr int kThreads = NW * 64;
     static constexpr int kTmMax = 16 * MB;
+    // With two row blocks the arithmetic phase of a step is long enough that issuing the next
+    // step's loads early pays (measured +4 %); with one it only adds bytes in flight beyond the
+    // 8 KiB per wave the memory system likes best (measured -1.5 %).
+    static constexpr bool kPipelined = MB > 1;
     static constexpr int kStreams = NW;
     // with 256 output columns per query row block set (D = 256, or two row blocks at D = 128) a
     // four-wave workgroup needs more than half of the register file per wave; it then runs as
@@ -190,31 +194,19 @@ struct GqaCore {
             }
             return x;
         };
-        // Per j and piece one fully coalesced wave-wide load over 4 rows, for K and for V.
-        auto load = [&](vvec(&kb)[NBLK][4], vvec(&vb)[NBLK][4], int step) {
-            const uint32_t off = v_lane_off + (uint32_t)step * (kTn * kRowBytes);
+        // Per j and piece one fully coalesced wave-wide load over 4 rows; `off` is the lane's byte
+        // offset of the step in the slab (an offset past the slab loads zeros without any traffic).
+        auto load_tile = [&](const buffer_rsrc& slab, vvec(&x)[NBLK][4], uint32_t off) {
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t o = off + (uint32_t)(blk * 16 + 4 * j) * kRowBytes;
-                    kb[blk][j] = load_row(k_slab, o);
-                }
-            }
-#pragma unroll
-            for (int blk = 0; blk < NBLK; ++blk) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t o = off + (uint32_t)(blk * 16 + 4 * j) * kRowBytes;
-                    vb[blk][j] = load_row(v_slab, o);
-                }
+                for (int j = 0; j < 4; ++j) x[blk][j] = load_row(slab, off + (uint32_t)(blk * 16 + 4 * j) * kRowBytes);
             }
         };
+        auto step_off = [&](int step) { return v_lane_off + (uint32_t)step * (kTn * kRowBytes); };
 
-        auto compute = [&](const vvec(&kraw)[NBLK][4], const vvec(&vb)[NBLK][4], int step) {
-            const int base = step * kTn + w * kCH;
-            // K rows -> wave-private LDS -> A-operand registers (lane r: token k_tok, lane group g: piece)
-            u32x4 kb[NBLK][kKC];
+        // K rows -> wave-private LDS (lane r: token k_tok, lane group g: piece); frees the registers
+        auto stage_k = [&](const vvec(&kraw)[NBLK][4]) {
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk) {
 #pragma unroll
@@ -226,6 +218,12 @@ struct GqaCore {
                 }
             }
             __builtin_amdgcn_wave_barrier();
+        };
+
+        // The staged K tile against Q, the online softmax, then P against the V tile in registers.
+        auto attend = [&](const vvec(&vb)[NBLK][4], int step) {
+            const int base = step * kTn + w * kCH;
+            u32x4 kb[NBLK][kKC];
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk) {
 #pragma unroll
@@ -313,28 +311,55 @@ struct GqaCore {
         // aligned spans sweep memory, and on this machine that lockstep is faster.)
         const int it_first = sg.local_iter;
         const int n_it = sg.local_iter_end - sg.local_iter;
-        auto iter_at = [&](int k) { return it_first + (k < n_it ? k : n_it - 1); };  // clamped: prefetches re-read
+        // Loads past the segment are issued unconditionally (a branch around them would make every
+        // later wait a wait for all loads) at an offset beyond the slab: zeros, no memory traffic.
+        constexpr uint32_t kPastSlab = 0xF0000000u;
+        auto off_at = [&](int k) { return k < n_it ? step_off(it_first + k) : kPastSlab; };
         if constexpr (DB) {
-            // Double-buffered walk: prefetches are unconditional so that the loads of the next
-            // step stay in flight across the arithmetic of this one.
+            // Double-buffered walk: the loads of the next step stay in flight across the
+            // arithmetic of this one.
             int k = 0;
-            load(kA, vA, iter_at(0));
+            load_tile(k_slab, kA, off_at(0));
+            load_tile(v_slab, vA, off_at(0));
             while (k < n_it) {
-                load(kB, vB, iter_at(k + 1));
-                compute(kA, vA, iter_at(k));
+                load_tile(k_slab, kB, off_at(k + 1));
+                load_tile(v_slab, vB, off_at(k + 1));
+                stage_k(kA);
+                attend(vA, it_first + k);
                 if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
-                load(kA, vA, iter_at(k + 2));
-                if (k + 1 < n_it) compute(kB, vB, iter_at(k + 1));
+                load_tile(k_slab, kA, off_at(k + 2));
+                load_tile(v_slab, vA, off_at(k + 2));
+                if (k + 1 < n_it) {
+                    stage_k(kB);
+                    attend(vB, it_first + k + 1);
+                }
                 k += 2;
             }
         } else {
-            // Single-buffered: a wave issues one step's loads, consumes them, then issues the
-            // next; the other waves of the compute unit cover its memory latency.
-            for (int k = 0; k < n_it; ++k) {
-                const int it = iter_at(k);
-                load(kA, vA, it);
-                compute(kA, vA, it);
-                if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+            if constexpr (!kPipelined) {
+                // One register buffer: a wave issues one step's loads, consumes them, then issues
+                // the next; the other waves of the compute unit cover its memory latency.
+                for (int k = 0; k < n_it; ++k) {
+                    load_tile(k_slab, kA, off_at(k));
+                    load_tile(v_slab, vA, off_at(k));
+                    stage_k(kA);
+                    attend(vA, it_first + k);
+                    if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+                }
+            } else {
+                // One register buffer, software-pipelined: the K registers are free as soon as the
+                // tile is staged in LDS, the V registers after the last PV contraction, so the next
+                // step's K loads are in flight across this step's arithmetic and its V loads across
+                // the next step's scores and softmax.
+                load_tile(k_slab, kA, off_at(0));
+                load_tile(v_slab, vA, off_at(0));
+                for (int k = 0; k < n_it; ++k) {
+                    stage_k(kA);
+                    load_tile(k_slab, kA, off_at(k + 1));
+                    attend(vA, it_first + k);
+                    load_tile(v_slab, vA, off_at(k + 1));
+                    if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+                }
             }
         }
 

@@ -136,9 +136,14 @@ __device__ __forceinline__ void merge_children_wide(const DecodeArgs& a, OwnPart
 // last and writes O = diag(l)^-1 O~ and L = m + log(l).  A block therefore only ever waits
 // for LOWER CTA ids, i.e. for workgroups the hardware dispatched before it, so every wait
 // ends even when the grid is larger than what is resident at once.
+// Threads of the LDS scratch of merge_children_wide: the workgroup for single-row cores, else a stub.
+template <class Core>
+constexpr int kWideThreads = Core::kTmMax == 1 ? Core::kThreads : 1;
+
 template <class Core, int CPT, int F>
 __device__ __forceinline__ void reduce_tile(const DecodeArgs& a, OwnPartial<CPT>& own, int g, int b, int h,
-                                            int first_cta, int last_cta, void* wide_scratch) {
+                                            int first_cta, int last_cta,
+                                            WideMergeScratch<kWideThreads<Core>>& wide_scratch) {
     constexpr int D = Core::kD;
     constexpr int THREADS = Core::kThreads;
     const int tid = threadIdx.x;
@@ -162,8 +167,7 @@ __device__ __forceinline__ void reduce_tile(const DecodeArgs& a, OwnPartial<CPT>
             while (remaining > 0) {
                 const int batch = remaining < kWide ? remaining : kWide;
                 wait_arrivals(a.flags, child, -(int)stride, batch, a.status, a.spin_limit);
-                merge_children_wide<THREADS, D>(a, own, child, -(int)stride, batch,
-                                                *static_cast<WideMergeScratch<THREADS>*>(wide_scratch));
+                merge_children_wide<THREADS, D>(a, own, child, -(int)stride, batch, wide_scratch);
                 child -= batch * (int)stride;
                 remaining -= batch;
             }
@@ -230,25 +234,19 @@ __global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_d
     __shared__ f32x4 parked_o[CPT * THREADS];
     __shared__ float parked_m[CPT * THREADS];
     __shared__ float parked_l[CPT * THREADS];
-    void* wide_scratch = nullptr;
-    if constexpr (Core::kTmMax == 1) {
-        __shared__ WideMergeScratch<THREADS> wide;
-        wide_scratch = &wide;
-    }
+    __shared__ WideMergeScratch<kWideThreads<Core>> wide_scratch;  // (a 24-byte stub for the MFMA cores)
 
-    // Read every scalar argument now, in one batch: left to itself the compiler loads each field
-    // right before its first use, and the span walk below becomes a chain of dependent round
-    // trips to the argument segment (measured: 1.5-1.8 us before the first K/V load is issued).
-    // The first entries of the two prefix tables are touched too, so that the table look-ups
-    // of small batches hit the scalar cache.
-    asm volatile("" ::"s"(a.q), "s"(a.k), "s"(a.v), "s"(a.out), "s"(a.lse), "s"(a.status), "s"(a.flags),
-                 "s"(a.partials), "s"(a.kv_seq_stride), "s"(a.total_rows), "s"(a.cta_clock), "s"(a.sched.total_iters),
-                 "s"(a.sched.iters_per_cta), "s"(a.Hq), "s"(a.Hkv), "s"(a.N_q), "s"(a.ragged_q), "s"(a.group), "s"(a.rows),
-                 "s"(a.C_m),
-                 "s"(a.T_m), "s"(a.causal), "s"(a.out16), "s"(a.slot), "s"(a.xcd_remap), "s"(a.spin_limit),
-                 "s"(a.has_empty), "s"(a.fanin), "s"(as_u32(a.scale_log2e)));
-    asm volatile("" ::"s"(a.sched.B), "s"(a.sched.Hkv), "s"(a.sched.T_n), "s"(a.sched.packed), "s"(a.sched.grid),
-                 "s"(a.sched.extra), "s"(a.sched.fixed_split), "s"(a.table.cu_iters[1]), "s"(a.table.cu_tok[1]));
+    // Touch every cache line of the argument block now, in one batch: left to itself the compiler
+    // loads each field right before its first use, and the span walk below becomes a chain of
+    // dependent misses to the argument segment (measured: 1.5-1.8 us before the first K/V load
+    // is issued).  One field per 64-byte line is enough (later reads hit the scalar cache) and
+    // keeps the scalar registers free; the first entries of the prefix tables are touched too,
+    // so that the table look-ups of small batches hit as well.
+    static_assert(offsetof(DecodeArgs, q) < 64 && offsetof(DecodeArgs, kv_seq_stride) / 64 == 1 &&
+                      offsetof(DecodeArgs, spin_limit) / 64 == 2 && offsetof(DecodeArgs, sched.iters_per_cta) / 64 == 3,
+                  "one touched field per line of the argument block");
+    asm volatile("" ::"s"(a.q), "s"(a.kv_seq_stride), "s"(a.spin_limit), "s"(a.sched.iters_per_cta),
+                 "s"(a.table.cu_iters[1]), "s"(a.table.cu_tok[1]));
 
     // CTA id.  The hardware deals consecutive workgroup ids round-robin to the
     // 8 XCDs; the optional remap makes the spans of one XCD contiguous so that

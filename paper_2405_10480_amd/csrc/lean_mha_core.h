@@ -14,8 +14,8 @@
 // of a workgroup and the workgroups of the grid are all merged with it.
 //
 // A workgroup step is one LeanTile of T_n = NW * U * 64/(D/8) tokens; wave w
-// takes the w-th slice.  The next step's K and V are already in flight in a
-// second register buffer while the current one is consumed.
+// takes the w-th slice.  The default shapes use one register buffer per wave; the
+// double-buffered shapes keep the next step's K and V in flight in a second one.
 #pragma once
 #include "lean_device.h"
 
@@ -69,18 +69,16 @@ struct MhaCore {
 
         u32x4 kA[U], vA[U], kB[U], vB[U];
 
-        // One wave-wide load per u: 64 lanes x 16 B = 1 KiB = kRPI whole rows.
-        auto load = [&](u32x4(&kb)[U], u32x4(&vb)[U], int step) {
-            const uint32_t off = lane_off + (uint32_t)step * (kTn * kRowBytes);
+        // One wave-wide load per u: 64 lanes x 16 B = 1 KiB = kRPI whole rows.  `off` is the lane's
+        // byte offset of the step in the slab (an offset past the slab loads zeros without any traffic).
+        auto load_tile = [&](const buffer_rsrc& slab, u32x4(&x)[U], uint32_t off) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) kb[u] = slab_load16(k_slab, off + u * 1024u);
-#pragma unroll
-            for (int u = 0; u < U; ++u) vb[u] = slab_load16(v_slab, off + u * 1024u);
+            for (int u = 0; u < U; ++u) x[u] = slab_load16(slab, off + u * 1024u);
         };
+        auto step_off = [&](int step) { return lane_off + (uint32_t)step * (kTn * kRowBytes); };
 
-        auto compute = [&](const u32x4(&kb)[U], const u32x4(&vb)[U], int step) {
-            const int tok0 = step * kTn + w * kCH + r;
-            float s[U];
+        // The lane's share of the U dot products q.k; frees the K registers.
+        auto scores = [&](const u32x4(&kb)[U], float(&s)[U]) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 float acc = dot2<DT>(kb[u].x, q.x, 0.f);
@@ -89,6 +87,11 @@ struct MhaCore {
                 acc = dot2<DT>(kb[u].w, q.w, acc);
                 s[u] = acc;
             }
+        };
+
+        // Row reduction of the scores, online softmax, O += p * V.
+        auto attend = [&](float(&s)[U], const u32x4(&vb)[U], int step) {
+            const int tok0 = step * kTn + w * kCH + r;
             float mx = -INFINITY;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -132,27 +135,41 @@ struct MhaCore {
         // aligned spans sweep memory, and on this machine that lockstep is faster.)
         const int it_first = sg.local_iter;
         const int n_it = sg.local_iter_end - sg.local_iter;
-        auto iter_at = [&](int k) { return it_first + (k < n_it ? k : n_it - 1); };  // clamped: prefetches re-read
+        // Loads past the segment are issued unconditionally (a branch around them would make every
+        // later wait a wait for all loads) at an offset beyond the slab: zeros, no memory traffic.
+        constexpr uint32_t kPastSlab = 0xF0000000u;
+        auto off_at = [&](int k) { return k < n_it ? step_off(it_first + k) : kPastSlab; };
+        float s[U];
         if constexpr (DB) {
-            // Double-buffered walk: prefetches are unconditional so that the loads of the next
-            // step stay in flight across the arithmetic of this one.
+            // Double-buffered walk: the loads of the next step stay in flight across the
+            // arithmetic of this one.
             int k = 0;
-            load(kA, vA, iter_at(0));
+            load_tile(k_slab, kA, off_at(0));
+            load_tile(v_slab, vA, off_at(0));
             while (k < n_it) {
-                load(kB, vB, iter_at(k + 1));
-                compute(kA, vA, iter_at(k));
+                load_tile(k_slab, kB, off_at(k + 1));
+                load_tile(v_slab, vB, off_at(k + 1));
+                scores(kA, s);
+                attend(s, vA, it_first + k);
                 if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
-                load(kA, vA, iter_at(k + 2));
-                if (k + 1 < n_it) compute(kB, vB, iter_at(k + 1));
+                load_tile(k_slab, kA, off_at(k + 2));
+                load_tile(v_slab, vA, off_at(k + 2));
+                if (k + 1 < n_it) {
+                    scores(kB, s);
+                    attend(s, vB, it_first + k + 1);
+                }
                 k += 2;
             }
         } else {
-            // Single-buffered: a wave issues one step's loads, consumes them, then issues the
-            // next; the other waves of the compute unit cover its memory latency.
+            // One register buffer: a wave issues one step's loads, consumes them, then issues the
+            // next; the other waves of the compute unit cover its memory latency.  (Issuing the
+            // next K loads right after the dot products was tried: 2 % slower, the memory system
+            // likes about 8 KiB in flight per wave best.)
             for (int k = 0; k < n_it; ++k) {
-                const int it = iter_at(k);
-                load(kA, vA, it);
-                compute(kA, vA, it);
+                load_tile(k_slab, kA, off_at(k));
+                load_tile(v_slab, vA, off_at(k));
+                scores(kA, s);
+                attend(s, vA, it_first + k);
                 if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
             }
         }
