@@ -328,3 +328,25 @@ def test_many_short_contexts_put_two_workgroups_on_a_unit():
     assert _plan([1000] * 32, 32, 8, 128, la.BF16, la.KV_PADDED, num_cus=256).grid == 256
     # an explicit request wins
     assert _plan([1000] * 256, 32, 8, 128, la.BF16, la.KV_PADDED, num_cus=256, ctas_per_cu=1).grid == 256
+
+
+def test_header_compiles_as_plain_c_and_matches_the_binding_structs(tmp_path):
+    # the boundary is a C ABI: the header must be valid C99, and the ctypes mirrors must have its layout
+    import ctypes
+    import subprocess
+
+    src = tmp_path / "abi.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "lean_attn.h"\n'
+        "int main(void) {\n"
+        '  printf("%zu %zu %zu ", sizeof(lean_attn_plan), sizeof(lean_attn_tuning), sizeof(lean_attn_problem));\n'
+        '  printf("%zu %zu %zu %zu\\n", offsetof(lean_attn_plan, total_iters), offsetof(lean_attn_tuning, cta_clock),\n'
+        "         offsetof(lean_attn_problem, kv_seq_stride), offsetof(lean_attn_problem, q_lens));\n"
+        "  return 0;\n}\n")
+    exe = tmp_path / "abi"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                           "-o", str(exe), str(src)])
+    got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
+    want = [ctypes.sizeof(la.Plan), ctypes.sizeof(la.Tuning), ctypes.sizeof(la.Problem), la.Plan.total_iters.offset,
+            la.Tuning.cta_clock.offset, la.Problem.kv_seq_stride.offset, la.Problem.q_lens.offset]
+    assert got == want
