@@ -85,9 +85,12 @@ def main() -> int:
     code = la.F16 if w.dtype == "f16" else la.BF16
 
     # Cache copies to rotate over: enough that a copy is evicted from the last-level cache
-    # before it is read again (at least 2x its capacity between reuses), at least two.
+    # before it is read again (at least 2x its capacity between reuses), and at least four while
+    # they fit in 16 GiB: the streaming rate depends by a few percent on where the driver happens
+    # to place the K and V buffers relative to each other, and a mean over four placements is
+    # steadier than one over two.
     one_copy = w.kv_bytes
-    copies = max(2, -(-2 * LLC_BYTES // one_copy) + 1)
+    copies = max(4 if 4 * one_copy <= (16 << 30) else 2, -(-2 * LLC_BYTES // one_copy) + 1)
     if one_copy * copies > 64 << 30:
         copies = 2
     inp = workloads.generate(w, device=dev)
