@@ -228,6 +228,9 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
  * q, k_cache, v_cache and out must be 16-byte aligned.
  * The first call per device and kernel variant reads the device's unit count and the
  * kernel's residency from the runtime (cached afterwards): make it outside graph capture.
+ * The schedule is computed on the host from seqlens and travels in the kernel arguments, so a
+ * launch captured into a HIP graph keeps the lengths it was captured with: re-capture (or
+ * update the kernel node) when they change.
  */
 int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache,
                      const int32_t* seqlens, float* out, float* lse, void* workspace,
