@@ -255,6 +255,32 @@ int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void
                      void* hip_stream);
 
 /*
+ * The same attention as lean_attn_attend, split in two for callers that replay a captured HIP
+ * graph while the sequence lengths change from step to step (a decode loop).
+ *
+ * lean_attn_attend_prepare is host-only: it validates the call, computes the schedule and writes
+ * everything the kernel needs into `block_host` (lean_attn_launch_block_size() bytes, 16-byte
+ * aligned; pinned host memory, e.g. hipHostMalloc, when lean_attn_launch is captured).  Nothing
+ * is launched.  Limits beyond lean_attn_attend's: B <= LEAN_ATTN_MAX_BATCH, tuning->tile_shape
+ * and tuning->fixed_split must be 0.  The launch shape written into the block depends only on
+ * the problem shape, never on seqlens: one workgroup per compute unit, surplus workgroups own
+ * empty spans.
+ *
+ * lean_attn_launch copies the block's arguments to `block_device` (device memory of the same
+ * size, asynchronously on the stream) and launches the kernel, which reads them from there.  Both
+ * steps can be captured.  To run new lengths through the same graph: wait until the previous
+ * replay has started its kernel (e.g. finished), call lean_attn_attend_prepare again with the
+ * same problem shape, buffers and block, replay.  On error nothing is launched and the block is
+ * left as it was.
+ */
+size_t lean_attn_launch_block_size(void);
+int lean_attn_attend_prepare(const lean_attn_problem* problem, const void* q, const void* k_cache,
+                             const void* v_cache, const int32_t* seqlens, void* out, float* lse,
+                             void* workspace, size_t workspace_bytes, const lean_attn_tuning* tuning,
+                             void* block_host);
+int lean_attn_launch(const void* block_host, void* block_device, void* hip_stream);
+
+/*
  * Measurement helper: one pass of 16-byte loads over `bytes` of device memory
  * by `grid` workgroups of 256 threads, without any arithmetic.  mode 0: each
  * workgroup reads one contiguous share (the access pattern of contiguous

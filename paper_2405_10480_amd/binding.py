@@ -108,6 +108,13 @@ def _load():
     lib.lean_attn_attend.restype = i32
     lib.lean_attn_attend.argtypes = [ctypes.POINTER(Problem), vp, vp, vp, vp, vp, vp, vp, sz,
                                      ctypes.POINTER(Tuning), vp]
+    lib.lean_attn_launch_block_size.restype = sz
+    lib.lean_attn_launch_block_size.argtypes = []
+    lib.lean_attn_attend_prepare.restype = i32
+    lib.lean_attn_attend_prepare.argtypes = [ctypes.POINTER(Problem), vp, vp, vp, vp, vp, vp, vp, sz,
+                                             ctypes.POINTER(Tuning), vp]
+    lib.lean_attn_launch.restype = i32
+    lib.lean_attn_launch.argtypes = [vp, vp, vp]
     lib.lean_attn_read_probe.restype = i32
     lib.lean_attn_read_probe.argtypes = [vp, sz, vp, i32, i32, vp]
     lib.lean_attn_strerror.restype = ctypes.c_char_p
@@ -300,6 +307,37 @@ def lean_attn_attend(problem: Problem, q, k_cache, v_cache, seqlens, out, worksp
     if prepare_only:
         return PreparedCall(_load().lean_attn_attend, args, (p, q, k_cache, v_cache, out, lse, workspace, arr, tuning))
     rc = _load().lean_attn_attend(*args)
+    if rc != OK:
+        raise LeanAttnError(rc)
+
+
+def lean_attn_launch_block_size() -> int:
+    return int(_load().lean_attn_launch_block_size())
+
+
+def lean_attn_attend_prepare(problem: Problem, q, k_cache, v_cache, seqlens, out, workspace, block_host, *, lse=None,
+                             tuning: Optional[Tuning] = None) -> None:
+    """Host-only: write the launch block for :func:`lean_attn_launch` (``block_host``: a pinned uint8 CPU tensor)."""
+    if block_host.is_cuda or block_host.numel() * block_host.element_size() < lean_attn_launch_block_size():
+        raise ValueError("block_host must be a host tensor of lean_attn_launch_block_size() bytes")
+    if len(seqlens) != problem.B:
+        raise ValueError("seqlens must have B entries")
+    arr = (ctypes.c_int32 * len(seqlens))(*[int(x) for x in seqlens])
+    rc = _load().lean_attn_attend_prepare(
+        ctypes.byref(problem), q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), arr, out.data_ptr(),
+        lse.data_ptr() if lse is not None else None, workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), _tuning_ptr(tuning), block_host.data_ptr())
+    if rc != OK:
+        raise LeanAttnError(rc)
+
+
+def lean_attn_launch(block_host, block_device, stream=None) -> None:
+    """Copy the prepared block to ``block_device`` and launch, on the current (or given) stream."""
+    if block_host.is_cuda or not block_device.is_cuda:
+        raise ValueError("block_host must be a (pinned) host tensor, block_device a device tensor")
+    if block_device.numel() * block_device.element_size() < lean_attn_launch_block_size():
+        raise ValueError("block_device must hold lean_attn_launch_block_size() bytes")
+    rc = _load().lean_attn_launch(block_host.data_ptr(), block_device.data_ptr(), _stream_handle(stream))
     if rc != OK:
         raise LeanAttnError(rc)
 

@@ -38,20 +38,23 @@ constexpr int kMaxProbeMode = 6;
 constexpr int kNumShapes = 6;
 
 struct Variant {
-    const void* fn;
+    const void* fn;           // arguments by value
+    const void* fn_indirect;  // arguments read from a device block (built for the default shapes only)
     int T_n;
     int threads;
 };
 
-template <class Core>
+template <class Core, bool INDIRECT = false>
 static Variant variant_of() {
-    return Variant{reinterpret_cast<const void*>(&lean_decode_kernel<Core>), Core::kTn, Core::kThreads};
+    const void* indirect = nullptr;
+    if constexpr (INDIRECT) indirect = reinterpret_cast<const void*>(&lean_decode_kernel_indirect<Core>);
+    return Variant{reinterpret_cast<const void*>(&lean_decode_kernel<Core>), indirect, Core::kTn, Core::kThreads};
 }
 
 template <int DT, int D>
 static Variant mha_shape(int shape) {  // <loads per lane per stream, waves, double-buffered>
     switch (shape) {
-        case 0: return variant_of<MhaCore<DT, D, 4, 4, false>>();
+        case 0: return variant_of<MhaCore<DT, D, 4, 4, false>, true>();
         case 1: return variant_of<MhaCore<DT, D, 8, 4, true>>();
         case 2: return variant_of<MhaCore<DT, D, 4, 4, true>>();
         case 3: return variant_of<MhaCore<DT, D, 8, 4, false>>();
@@ -67,12 +70,12 @@ static Variant gqa_shape(int shape) {  // <16-token blocks per wave per step, wa
     if (shape == 0 && D == 64) shape = 4;
     if (shape == 0 && D == 256) shape = 5;
     switch (shape) {
-        case 0: return variant_of<GqaCore<DT, D, 1, 4, false>>();
+        case 0: return variant_of<GqaCore<DT, D, 1, 4, false>, D == 128>();
         case 1: return variant_of<GqaCore<DT, D, 2, 4, true>>();
         case 2: return variant_of<GqaCore<DT, D, 1, 4, true>>();
         case 3: return variant_of<GqaCore<DT, D, 1, 8, true>>();
-        case 4: return variant_of<GqaCore<DT, D, 1, 8, false>>();
-        default: return variant_of<GqaCore<DT, D, 2, 4, false>>();
+        case 4: return variant_of<GqaCore<DT, D, 1, 8, false>, D == 64>();
+        default: return variant_of<GqaCore<DT, D, 2, 4, false>, D == 256>();
     }
 }
 
@@ -82,10 +85,10 @@ static Variant gqa_shape_two_blocks(int shape) {
     if (shape == 0) shape = D == 64 ? 1 : 5;  // measured best: two token blocks per wave, double-buffered at D = 64
     switch (shape) {
         case 0: return variant_of<GqaCore<DT, D, 1, 4, false, 2>>();
-        case 1: return variant_of<GqaCore<DT, D, 2, 4, true, 2>>();
+        case 1: return variant_of<GqaCore<DT, D, 2, 4, true, 2>, D == 64>();
         case 2: return variant_of<GqaCore<DT, D, 1, 4, true, 2>>();
         case 3: case 4: return variant_of<GqaCore<DT, D, 1, 8, false, 2>>();
-        default: return variant_of<GqaCore<DT, D, 2, 4, false, 2>>();
+        default: return variant_of<GqaCore<DT, D, 2, 4, false, 2>, D == 128>();
     }
 }
 
@@ -205,8 +208,10 @@ static lean_attn_problem decode_problem(int B, int Hq, int Hkv, int D, int dtype
 // The host scheduler: per-sequence tile counts, total iterations, grid, spans.
 // O(B) integer work; nothing here touches the device unless the unit count has
 // to be read.
+// full_grid: the grid is units x 1 whatever the lengths are (even when that exceeds the iteration
+// count: the surplus workgroups own empty spans), so that a launch captured once serves any lengths.
 static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, const lean_attn_tuning* tn,
-                         lean_attn_plan* plan, Sched* sched, SchedTable* table) {
+                         lean_attn_plan* plan, Sched* sched, SchedTable* table, bool full_grid = false) {
     if (!seqlens || !plan) return LEAN_ATTN_ERR_NULL_POINTER;
     int rc = check_problem(p);
     if (rc != LEAN_ATTN_OK) return rc;
@@ -272,7 +277,8 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
     // round trip); a second workgroup on the unit fills those bubbles (measured: 3-5 % faster
     // at 1000 tokens per sequence, even at 2000, 1 % slower at 4000).
     int default_per_cu = kDefaultCtasPerCu;
-    if (nonempty > 0 && toks / nonempty <= kShortContextTokens && (int64_t)nonempty * heads >= 2 * (int64_t)cus)
+    if (!full_grid && nonempty > 0 && toks / nonempty <= kShortContextTokens &&
+        (int64_t)nonempty * heads >= 2 * (int64_t)cus)
         default_per_cu = 2;
     if (hw_per_cu > 0) {
         if (per_cu <= 0) per_cu = hw_per_cu < default_per_cu ? hw_per_cu : default_per_cu;
@@ -287,7 +293,7 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
     int64_t G = (int64_t)cus * per_cu * (t.grid_multiple > 0 ? t.grid_multiple : kDefaultGridMultiple);
     if (t.grid > 0) G = t.grid;
     if (G > LEAN_ATTN_MAX_GRID) G = LEAN_ATTN_MAX_GRID;
-    if (G > I) G = I;
+    if (G > I && !full_grid) G = I;
     if (G < 1) G = 1;
 
     // Baseline schedule: fixed split.  With no factor given, split so that one wave of
@@ -437,33 +443,38 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
     return n;
 }
 
-// One launch: at most LEAN_ATTN_MAX_BATCH sequences.  `tok_base` / `tok_total`: position of this
-// batch's first token in a PACKED cache that holds `tok_total` tokens per head (0 and the batch's
-// own total when the batch is the whole cache).
-static int launch_one(const lean_attn_problem& p, const void* q, const void* k_cache, const void* v_cache,
-                      const int32_t* seqlens, void* out, float* lse, void* workspace, const lean_attn_tuning* tuning,
-                      hipStream_t stream, int64_t tok_base, int64_t tok_total) {
+static int check_lengths(const lean_attn_problem& p, const int32_t* seqlens, int64_t* tok_total) {
+    int64_t total = 0;
+    for (int b = 0; b < p.B; ++b) {
+        const int64_t n = seqlens[b];
+        const int q_len = p.q_lens ? p.q_lens[b] : p.N_q;
+        if (n < 0 || n * p.D * 2 > INT32_MAX) return LEAN_ATTN_ERR_SEQLEN;
+        if (p.causal && n != 0 && n < q_len) return LEAN_ATTN_ERR_SEQLEN;
+        if (p.kv_layout == LEAN_ATTN_KV_PADDED && p.kv_seq_stride < n) return LEAN_ATTN_ERR_SEQLEN;
+        total += n;
+        if (total > INT32_MAX) return LEAN_ATTN_ERR_SEQLEN;
+    }
+    *tok_total = total;
+    return LEAN_ATTN_OK;
+}
+
+// The arguments of one launch (at most LEAN_ATTN_MAX_BATCH sequences): schedule, kernel variant,
+// argument block.  `tok_base` / `tok_total`: position of this batch's first token in a PACKED cache
+// that holds `tok_total` tokens per head (0 and the batch's own total when the batch is the whole
+// cache).
+static int build_launch(const lean_attn_problem& p, const void* q, const void* k_cache, const void* v_cache,
+                        const int32_t* seqlens, void* out, float* lse, void* workspace, const lean_attn_tuning* tuning,
+                        int64_t tok_base, int64_t tok_total, bool full_grid, lean_attn_plan* plan, Variant* var,
+                        DecodeArgs* args) {
     const int B = p.B, D = p.D;
-    lean_attn_plan plan;
-    DecodeArgs a;
-    int rc = make_schedule(p, seqlens, tuning, &plan, &a.sched, &a.table);
+    DecodeArgs& a = *args;
+    int rc = make_schedule(p, seqlens, tuning, plan, &a.sched, &a.table, full_grid);
     if (rc != LEAN_ATTN_OK) return rc;
     int32_t has_empty = 0;
     for (int b = 0; b < B; ++b) {
         if (seqlens[b] == 0) has_empty = 1;
     }
-    const int out16 = p.out_dtype == LEAN_ATTN_OUT_AS_INPUT;
-    if (plan.total_iters == 0) {  // every sequence is empty
-        const int64_t rows = (int64_t)a.table.cu_q[B] * p.Hq;
-        const int row_words = out16 ? D / 2 : D;
-        if (rows == 0) return LEAN_ATTN_OK;
-        hipLaunchKernelGGL(lean_zero_rows_kernel, dim3((unsigned)((rows * row_words + 255) / 256)), dim3(256), 0,
-                           stream, (uint32_t*)out, lse, rows, row_words);
-        return hipGetLastError() == hipSuccess ? LEAN_ATTN_OK : LEAN_ATTN_ERR_HIP;
-    }
-
-    Variant var;
-    if (!pick_variant(plan.kernel, p.dtype, D, tuning ? tuning->tile_shape : 0, plan.T_m, &var))
+    if (!pick_variant(plan->kernel, p.dtype, D, tuning ? tuning->tile_shape : 0, plan->T_m, var))
         return LEAN_ATTN_ERR_UNSUPPORTED;
 
     const RowBlocks rb = row_blocks(p);
@@ -489,18 +500,37 @@ static int launch_one(const lean_attn_problem& p, const void* q, const void* k_c
     a.C_m = rb.C_m;
     a.T_m = rb.T_m;
     a.causal = p.causal;
-    a.out16 = out16;
+    a.out16 = p.out_dtype == LEAN_ATTN_OUT_AS_INPUT;
     a.slot = slot_floats(rb.T_m, D);
     // the remap permutes span ids against dispatch order: only safe while the whole grid is resident
-    a.xcd_remap = (tuning && tuning->xcd_remap == 2 && plan.grid <= plan.max_resident) ? 1 : 0;
+    a.xcd_remap = (tuning && tuning->xcd_remap == 2 && plan->grid <= plan->max_resident) ? 1 : 0;
     a.spin_limit = (tuning && tuning->spin_limit > 0) ? tuning->spin_limit : (1 << 22);
     a.has_empty = has_empty;
     // single-row tiles merge a whole level of up to 32 partials in one round trip (see merge_children_wide)
     a.fanin = (tuning && tuning->merge_fanin >= 2) ? tuning->merge_fanin
-                                                   : (plan.kernel == 0 ? kDefaultFaninSingleRow : kDefaultFanin);
+                                                   : (plan->kernel == 0 ? kDefaultFaninSingleRow : kDefaultFanin);
     a.cta_clock = tuning ? (unsigned long long*)tuning->cta_clock : nullptr;
     a.scale_log2e = p.scale * 1.4426950408889634f;
+    return LEAN_ATTN_OK;
+}
 
+static int launch_one(const lean_attn_problem& p, const void* q, const void* k_cache, const void* v_cache,
+                      const int32_t* seqlens, void* out, float* lse, void* workspace, const lean_attn_tuning* tuning,
+                      hipStream_t stream, int64_t tok_base, int64_t tok_total) {
+    lean_attn_plan plan;
+    Variant var;
+    DecodeArgs a;
+    int rc = build_launch(p, q, k_cache, v_cache, seqlens, out, lse, workspace, tuning, tok_base, tok_total, false,
+                          &plan, &var, &a);
+    if (rc != LEAN_ATTN_OK) return rc;
+    if (plan.total_iters == 0) {  // every sequence is empty
+        const int64_t rows = (int64_t)a.table.cu_q[p.B] * p.Hq;
+        const int row_words = a.out16 ? p.D / 2 : p.D;
+        if (rows == 0) return LEAN_ATTN_OK;
+        hipLaunchKernelGGL(lean_zero_rows_kernel, dim3((unsigned)((rows * row_words + 255) / 256)), dim3(256), 0,
+                           stream, (uint32_t*)out, lse, rows, row_words);
+        return hipGetLastError() == hipSuccess ? LEAN_ATTN_OK : LEAN_ATTN_ERR_HIP;
+    }
     void* params[] = {&a};
     if (hipLaunchKernel(var.fn, dim3(plan.grid), dim3(var.threads), params, 0, stream) != hipSuccess) {
         (void)hipGetLastError();
@@ -508,6 +538,16 @@ static int launch_one(const lean_attn_problem& p, const void* q, const void* k_c
     }
     return LEAN_ATTN_OK;
 }
+
+// What lean_attn_attend_prepare writes into the caller's host block and lean_attn_launch reads.
+struct LaunchBlock {
+    uint64_t magic;
+    const void* fn;  // lean_decode_kernel_indirect<...>
+    uint32_t grid, threads;
+    uint64_t reserved;
+    alignas(16) DecodeArgs args;  // the part that is copied to the device
+};
+constexpr uint64_t kBlockMagic = 0x314b4c424e41454cull;  // "LEANBLK1"
 
 int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void* k_cache, const void* v_cache,
                      const int32_t* seqlens, void* out, float* lse, void* workspace, size_t workspace_bytes,
@@ -522,15 +562,8 @@ int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void
         return LEAN_ATTN_ERR_WORKSPACE;
     // every length is checked before the first launch: on error nothing runs
     int64_t tok_total = 0;
-    for (int b = 0; b < p.B; ++b) {
-        const int64_t n = seqlens[b];
-        const int q_len = p.q_lens ? p.q_lens[b] : p.N_q;
-        if (n < 0 || n * p.D * 2 > INT32_MAX) return LEAN_ATTN_ERR_SEQLEN;
-        if (p.causal && n != 0 && n < q_len) return LEAN_ATTN_ERR_SEQLEN;
-        if (p.kv_layout == LEAN_ATTN_KV_PADDED && p.kv_seq_stride < n) return LEAN_ATTN_ERR_SEQLEN;
-        tok_total += n;
-        if (tok_total > INT32_MAX) return LEAN_ATTN_ERR_SEQLEN;
-    }
+    rc = check_lengths(p, seqlens, &tok_total);
+    if (rc != LEAN_ATTN_OK) return rc;
     hipStream_t stream = (hipStream_t)hip_stream;
     if (p.B <= LEAN_ATTN_MAX_BATCH)
         return launch_one(p, q, k_cache, v_cache, seqlens, out, lse, workspace, tuning, stream, 0, tok_total);
@@ -570,6 +603,59 @@ int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void
         }
         tok_base += chunk_toks;
         row_base += chunk_q * p.Hq;
+    }
+    return LEAN_ATTN_OK;
+}
+
+size_t lean_attn_launch_block_size(void) { return sizeof(LaunchBlock); }
+
+int lean_attn_attend_prepare(const lean_attn_problem* problem, const void* q, const void* k_cache,
+                             const void* v_cache, const int32_t* seqlens, void* out, float* lse, void* workspace,
+                             size_t workspace_bytes, const lean_attn_tuning* tuning, void* block_host) {
+    if (!problem || !q || !k_cache || !v_cache || !seqlens || !out || !workspace || !block_host)
+        return LEAN_ATTN_ERR_NULL_POINTER;
+    const lean_attn_problem& p = *problem;
+    int rc = check_problem(p);  // one launch: at most LEAN_ATTN_MAX_BATCH sequences
+    if (rc != LEAN_ATTN_OK) return rc;
+    if ((((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out | (uintptr_t)block_host) & 15) != 0)
+        return LEAN_ATTN_ERR_BAD_SHAPE;
+    if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < lean_attn_problem_workspace_size(problem))
+        return LEAN_ATTN_ERR_WORKSPACE;
+    if (tuning && (tuning->fixed_split != 0 || tuning->tile_shape != 0)) return LEAN_ATTN_ERR_TUNING;
+    int64_t tok_total = 0;
+    rc = check_lengths(p, seqlens, &tok_total);
+    if (rc != LEAN_ATTN_OK) return rc;
+    LaunchBlock blk;  // built aside: the caller's block is only touched when everything is valid
+    lean_attn_plan plan;
+    Variant var;
+    rc = build_launch(p, q, k_cache, v_cache, seqlens, out, lse, workspace, tuning, 0, tok_total, true, &plan, &var,
+                      &blk.args);
+    if (rc != LEAN_ATTN_OK) return rc;
+    if (!var.fn_indirect) return LEAN_ATTN_ERR_UNSUPPORTED;
+    blk.magic = kBlockMagic;
+    blk.fn = var.fn_indirect;
+    blk.grid = (uint32_t)plan.grid;
+    blk.threads = (uint32_t)var.threads;
+    blk.reserved = 0;
+    std::memcpy(block_host, &blk, sizeof blk);
+    return LEAN_ATTN_OK;
+}
+
+int lean_attn_launch(const void* block_host, void* block_device, void* hip_stream) {
+    if (!block_host || !block_device) return LEAN_ATTN_ERR_NULL_POINTER;
+    if ((((uintptr_t)block_host | (uintptr_t)block_device) & 15) != 0) return LEAN_ATTN_ERR_BAD_SHAPE;
+    const LaunchBlock* blk = static_cast<const LaunchBlock*>(block_host);
+    if (blk->magic != kBlockMagic || !blk->fn || blk->grid == 0 || blk->grid > LEAN_ATTN_MAX_GRID)
+        return LEAN_ATTN_ERR_BAD_SHAPE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (hipMemcpyAsync(block_device, &blk->args, sizeof(DecodeArgs), hipMemcpyHostToDevice, stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return LEAN_ATTN_ERR_HIP;
+    }
+    void* params[] = {&block_device};
+    if (hipLaunchKernel(blk->fn, dim3(blk->grid), dim3(blk->threads), params, 0, stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return LEAN_ATTN_ERR_HIP;
     }
     return LEAN_ATTN_OK;
 }

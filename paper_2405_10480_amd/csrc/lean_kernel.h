@@ -222,7 +222,7 @@ __device__ __forceinline__ void reduce_tile(const DecodeArgs& a, OwnPartial<CPT>
 }
 
 template <class Core>
-__global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_decode_kernel(const DecodeArgs a) {
+__device__ __forceinline__ void lean_decode_body(const DecodeArgs& a) {
     constexpr int D = Core::kD;
     constexpr int THREADS = Core::kThreads;
     constexpr int CPT = (Core::kTmMax * D / 4 + THREADS - 1) / THREADS;  // float4 chunks per thread
@@ -348,6 +348,20 @@ __global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_d
         reduce_tile<Core, CPT, F>(a, own, g, parked_b, parked_h, parked_first, g, wide_scratch);
     }
     stamp(a, g, 3);
+}
+
+// The arguments travel by value in the kernel argument segment ...
+template <class Core>
+__global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_decode_kernel(const DecodeArgs a) {
+    lean_decode_body<Core>(a);
+}
+
+// ... or are read from a block in device memory that the host rewrites between launches: the same
+// captured launch then serves new sequence lengths.
+template <class Core>
+__global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_decode_kernel_indirect(
+    const DecodeArgs* __restrict__ block) {
+    lean_decode_body<Core>(*block);
 }
 
 // Clears flags and status of a fresh workspace (a fill kernel: safe under graph capture).

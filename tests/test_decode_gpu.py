@@ -709,3 +709,59 @@ def test_seeded_random_problems_against_the_oracle():
         else:
             half_ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -11
             assert np.all(np.abs(got - want) <= TIGHT_ABS + half_ulp * np.abs(want) * 1.01 + 1e-7), label
+
+
+@pytest.mark.parametrize("group,N_q", [(1, 1), (4, 1), (8, 3)])
+def test_one_captured_graph_serves_changing_lengths(group, N_q):
+    # a decode loop: the launch is captured once; before each replay the host rewrites the argument
+    # block for the new lengths (the grid never depends on them)
+    Hkv, D, B, stride = 2, 128, 4, 6000
+    causal = N_q > 1
+    w0 = workloads.Workload("graph_loop", B, Hkv * group, Hkv, D, "bf16", (stride,) * B, workloads.KV_PADDED, seed=120 + group,
+                            N_q=N_q, causal=causal)
+    inp = workloads.generate(w0, device="cuda")          # a cache of `stride` rows per sequence, filled
+    pr = _problem_of(w0)
+    ws = torch.empty(la.lean_attn_problem_workspace_size(pr), dtype=torch.uint8, device="cuda")
+    la.lean_attn_workspace_init(ws)
+    out = torch.full((B, N_q, w0.Hq, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((B, N_q, w0.Hq), float("nan"), dtype=torch.float32, device="cuda")
+    nbytes = la.lean_attn_launch_block_size()
+    block_host = torch.zeros(nbytes, dtype=torch.uint8).pin_memory()
+    block_dev = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    q4 = inp.q.view(B, N_q, w0.Hq, D)
+
+    steps = [[3000, 17, 5999, 64], [3001, 18, 6000, 65], [0, N_q, 1500, 1], [0, 0, 0, 0], [6000, 6000, 6000, 6000],
+             [N_q, 1000, 0, 4097]]
+    steps = [[n if (n == 0 or n >= N_q) else N_q for n in s] for s in steps]
+    # eager first (also the first call on this device: runtime queries happen outside the capture)
+    la.lean_attn_attend_prepare(pr, q4, inp.k, inp.v, steps[0], out, ws, block_host, lse=lse)
+    la.lean_attn_launch(block_host, block_dev)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        la.lean_attn_launch(block_host, block_dev)
+    for seqlens in steps:
+        la.lean_attn_attend_prepare(pr, q4, inp.k, inp.v, seqlens, out, ws, block_host, lse=lse)
+        out.fill_(float("nan"))
+        lse.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert la.lean_attn_workspace_status(ws) == 0
+        want, want_lse = oracle.attention(q4, inp.k, inp.v, seqlens, N_q=N_q, Hq=w0.Hq, Hkv=Hkv, D=D, scale=w0.scale,
+                                          causal=causal, n_stride=stride)
+        _check(out.cpu().numpy(), lse.cpu().numpy(), want, want_lse, f"graph loop g={group} N_q={N_q} {seqlens}")
+        # the same lengths through the one-call entry point: bit-identical when it picks the same grid
+        ref = torch.empty_like(out)
+        la.lean_attn_attend(pr, q4, inp.k, inp.v, seqlens, ref, ws, tuning=la.Tuning(ctas_per_cu=1))
+        torch.cuda.synchronize()
+        plan = la.lean_attn_problem_schedule(pr, seqlens, la.Tuning(ctas_per_cu=1))
+        if plan.grid == 256 and plan.total_iters > 0:
+            assert torch.equal(out, ref)
+    # a refused update leaves the block launchable as it was
+    with pytest.raises(la.LeanAttnError):
+        la.lean_attn_attend_prepare(pr, q4, inp.k, inp.v, [1, 2, 3, stride + 1], out, ws, block_host)
+    graph.replay()
+    torch.cuda.synchronize()
+    want, _ = oracle.attention(q4, inp.k, inp.v, steps[-1], N_q=N_q, Hq=w0.Hq, Hkv=Hkv, D=D, scale=w0.scale,
+                               causal=causal, n_stride=stride)
+    _check(out.cpu().numpy(), None, want, None, "after a refused update")

@@ -1,6 +1,7 @@
 """Host logic of the HIP library, run without a GPU: the stream-K scheduler and
 span walk (the same code the kernel executes), argument checking, and the
 exported symbols of the C ABI.  No compute entry point is called here."""
+import ctypes
 import math
 import os
 import re
@@ -350,3 +351,48 @@ def test_header_compiles_as_plain_c_and_matches_the_binding_structs(tmp_path):
     want = [ctypes.sizeof(la.Plan), ctypes.sizeof(la.Tuning), ctypes.sizeof(la.Problem), la.Plan.total_iters.offset,
             la.Tuning.cta_clock.offset, la.Problem.kv_seq_stride.offset, la.Problem.q_lens.offset]
     assert got == want
+
+
+def test_prepare_writes_a_launch_block_whose_grid_does_not_depend_on_the_lengths():
+    # host-only: no pointer is dereferenced, so made-up (aligned, non-null) addresses do
+    import struct
+
+    import torch
+
+    lib = ctypes.CDLL(la.library_path())
+    lib.lean_attn_launch_block_size.restype = ctypes.c_size_t
+    size = lib.lean_attn_launch_block_size()
+    assert size == la.lean_attn_launch_block_size() and size % 16 == 0 and size < 4096
+    pr = _problem(3, 1, 16, 2, 128, stride=200000)
+    ws_bytes = la.lean_attn_problem_workspace_size(pr)
+
+    class Fake:  # stands in for a device tensor: only data_ptr/numel/element_size are used
+        def __init__(self, addr, n=0):
+            self.addr, self.n = addr, n
+        def data_ptr(self):
+            return self.addr
+        def numel(self):
+            return self.n
+        def element_size(self):
+            return 1
+
+    q, k, v, out, ws = Fake(0x10000), Fake(0x20000), Fake(0x30000), Fake(0x40000), Fake(0x100000, ws_bytes)
+    block = torch.zeros(size, dtype=torch.uint8)
+    tn = la.Tuning(num_cus=256)
+    grids = []
+    for seqlens in ([5000, 0, 777], [1, 1, 1], [0, 0, 0], [200000, 3, 64]):
+        la.lean_attn_attend_prepare(pr, q, k, v, seqlens, out, ws, block, tuning=tn)
+        magic, fn, grid, threads = struct.unpack_from("<QQII", block.numpy().tobytes(), 0)
+        assert magic == int.from_bytes(b"LEANBLK1", "little") and fn != 0 and threads == 256
+        grids.append(grid)
+    assert grids == [256] * 4          # one workgroup per unit, even with 3 iterations or none at all
+    before = block.clone()
+    for bad_kwargs, seqlens, status in ((dict(tile_shape=1), [10, 10, 10], -8), (dict(fixed_split=2), [10, 10, 10], -8),
+                                        (dict(), [10, -1, 10], -5)):
+        with pytest.raises(la.LeanAttnError) as e:
+            la.lean_attn_attend_prepare(pr, q, k, v, seqlens, out, ws, block, tuning=la.Tuning(num_cus=256, **bad_kwargs))
+        assert e.value.status == status
+        assert torch.equal(block, before), "a refused call must leave the block as it was"
+    with pytest.raises(la.LeanAttnError) as e:
+        la.lean_attn_attend_prepare(_problem(300, 1, 16, 2, 128, stride=8), q, k, v, [5] * 300, out, ws, block, tuning=tn)
+    assert e.value.status == -6
