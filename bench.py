@@ -64,6 +64,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--context-sweep", action="store_true",
+                    help="also time contexts 4k..256k at D=128 bf16 (MHA 32 heads, GQA 64/8; batch 1 and 4) and "
+                         "report them under \"context_sweep\"")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (multi-GPU sharding is design-only)",
@@ -289,6 +292,50 @@ def main() -> int:
         "paper_context": "LeanAttention reports speedups over FlashDecoding only (avg 1.73x, up to 2.18x at 256k, "
                          "A100-80GB, FP16->FP32); no absolute number for this metric",
     }
+
+    if args.context_sweep:
+        # The streaming rate over the context range of the target (4k .. 256k tokens): K steps back
+        # to back under one event pair per point, prepared calls, cache copies rotated so that no
+        # point is served from the last-level cache.
+        del ks, vs, steps_prepared
+        torch.cuda.empty_cache()
+        sweep = []
+        for (B_s, Hq_s, Hkv_s) in ((1, 32, 32), (1, 64, 8), (4, 32, 32), (4, 64, 8)):
+            for ctx in (4096, 8192, 16384, 32768, 65536, 131072, 262144):
+                ws_ = workloads.Workload(f"sweep_b{B_s}_h{Hq_s}_{Hkv_s}_n{ctx}", B_s, Hq_s, Hkv_s, 128, "bf16",
+                                         (ctx,) * B_s, workloads.KV_PADDED, seed=7)
+                if ws_.kv_bytes > (4 << 30):
+                    continue
+                n_copies = max(2, min(64, -(-2 * LLC_BYTES // ws_.kv_bytes) + 1))
+                inp_s = workloads.generate(ws_, device=dev)
+                k_s = [inp_s.k] + [inp_s.k.clone() for _ in range(n_copies - 1)]
+                v_s = [inp_s.v] + [inp_s.v.clone() for _ in range(n_copies - 1)]
+                out_s = torch.empty(B_s, Hq_s, 128, dtype=torch.float32, device=dev)
+                wsp = torch.empty(la.lean_attn_workspace_size(B_s, Hq_s, Hkv_s, 128, la.BF16), dtype=torch.uint8, device=dev)
+                la.lean_attn_workspace_init(wsp)
+                calls = [la.lean_attn_decode(inp_s.q, k_s[j], v_s[j], inp_s.seqlens, out_s, wsp, Hkv=Hkv_s,
+                                             kv_layout=ws_.kv_layout, kv_seq_stride=ws_.n_stride, scale=ws_.scale,
+                                             prepare_only=True) for j in range(n_copies)]
+                reps = max(20, min(200, int(0.05 / (ws_.kv_bytes / 6e12))))
+                for i in range(20):
+                    calls[i % n_copies]()
+                torch.cuda.synchronize()
+                rounds = []
+                for _ in range(3):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for i in range(reps):
+                        calls[i % n_copies]()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    rounds.append(e0.elapsed_time(e1) / reps)
+                ms = sorted(rounds)[1]
+                assert la.lean_attn_workspace_status(wsp) == 0
+                sweep.append({"B": B_s, "Hq": Hq_s, "Hkv": Hkv_s, "context": ctx, "kv_bytes": ws_.kv_bytes,
+                              "us_per_step": round(ms * 1e3, 2), "GBps": round(ws_.kv_bytes / ms / 1e6, 1),
+                              "pct_of_hbm_peak": round(100.0 * ws_.kv_bytes / ms / 1e6 / HBM_PEAK_GBPS, 1)})
+                del inp_s, k_s, v_s, calls
+        result["context_sweep"] = sweep
 
     if not args.no_cpu_baseline:
         import oracle
