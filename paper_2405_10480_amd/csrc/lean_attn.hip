@@ -425,8 +425,7 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
     const int64_t begin = it;
     Segment sg;
     while (it < end) {
-        sg = it == begin ? locate_start(s, t, it, end) : locate_next_start(s, t, sg, end);  // as the kernel walks
-        locate_peers(s, sg, g);
+        sg = it == begin ? locate(s, t, it, end) : locate_next(s, t, sg, g, end);  // as the kernel walks
         if (n < max_segments) {
             int64_t* rec = segments + 8 * (int64_t)n;
             rec[0] = sg.tile_idx;

@@ -23,8 +23,7 @@ inline __host__ __device__ int slot_floats(int T_m, int D) {
     return (n + 63) & ~63;  // 256-byte slots
 }
 
-// Everything but the prefix tables: 216 bytes that the kernel reads into scalar registers once.
-struct DecodeScalars {
+struct DecodeArgs {
     const uint16_t* q;
     const uint16_t* k;
     const uint16_t* v;
@@ -53,39 +52,8 @@ struct DecodeScalars {
     unsigned long long* cta_clock;  // optional trace, 8 words per CTA, may be null
     float scale_log2e;     // scale * log2(e): scores live in the base-2 domain
     Sched sched;
-};
-
-// The kernel argument block as the host builds it.
-struct DecodeArgs : DecodeScalars {
     SchedTable table;
 };
-
-// The same block as the device code sees it: the scalars live in registers (copied once at kernel
-// entry, see pin_scalars), the prefix tables stay where the launch put them.
-struct Args : DecodeScalars {
-    const SchedTable& table;
-    __device__ __forceinline__ Args(const DecodeArgs& block) : DecodeScalars(block), table(block.table) {}
-};
-
-// Left to itself the compiler re-reads an argument field from the argument segment right before
-// each use; every such read is a round trip to the scalar cache (about 50 ns), and the span walk
-// before the first K/V load chains some twenty of them (1.2 us measured).  Passing each field
-// through an empty asm makes it a register value that cannot be re-read: all fields are fetched in
-// one batch at kernel entry and kept (the compiler parks what does not fit in lanes of a vector
-// register).
-template <class T>
-__device__ __forceinline__ void pin(T& x) {
-    asm volatile("" : "+s"(x));
-}
-__device__ __forceinline__ void pin_scalars(Args& a) {
-    pin(a.q); pin(a.k); pin(a.v); pin(a.out); pin(a.lse); pin(a.status); pin(a.flags); pin(a.partials);
-    pin(a.kv_seq_stride); pin(a.total_rows);
-    pin(a.Hq); pin(a.Hkv); pin(a.N_q); pin(a.ragged_q); pin(a.group); pin(a.rows); pin(a.C_m); pin(a.T_m);
-    pin(a.causal); pin(a.out16); pin(a.slot); pin(a.xcd_remap); pin(a.spin_limit); pin(a.has_empty);
-    pin(a.fanin); pin(a.cta_clock); pin(a.scale_log2e);
-    pin(a.sched.B); pin(a.sched.Hkv); pin(a.sched.T_n); pin(a.sched.packed); pin(a.sched.grid);
-    pin(a.sched.extra); pin(a.sched.total_iters); pin(a.sched.iters_per_cta); pin(a.sched.fixed_split);
-}
 
 // The rows of output tile (b, head) where head = hk * C_m + mb: KV head hk, row block mb.
 struct TileRows {
@@ -95,7 +63,7 @@ struct TileRows {
     int q_len;   // query tokens of the sequence
     int64_t q0;  // index of the sequence's first query token among all query tokens
 };
-__device__ __forceinline__ TileRows tile_rows(const Args& a, int b, int head) {
+__device__ __forceinline__ TileRows tile_rows(const DecodeArgs& a, int b, int head) {
     TileRows t;
     t.hk = a.C_m == 1 ? head : head / a.C_m;
     t.rho0 = (head - t.hk * a.C_m) * a.T_m;
@@ -112,7 +80,7 @@ __device__ __forceinline__ TileRows tile_rows(const Args& a, int b, int head) {
 }
 // Index into the q / out / lse rows (query token, query head) of row rho of the tile's KV head;
 // *token gets the query token within its sequence.
-__device__ __forceinline__ int64_t query_row(const Args& a, const TileRows& t, int rho, int* token) {
+__device__ __forceinline__ int64_t query_row(const DecodeArgs& a, const TileRows& t, int rho, int* token) {
     const int i = (a.N_q == 1 && !a.ragged_q) ? 0 : rho / a.group;
     *token = i;
     return (t.q0 + i) * a.Hq + (int64_t)t.hk * a.group + (rho - i * a.group);
@@ -268,7 +236,7 @@ __device__ __forceinline__ void wait_arrivals(uint32_t* flags, int first, int st
 
 // Optional per-CTA trace: 8 uint64 per CTA: timestamps (100 MHz) at kernel entry, end of
 // streaming, end of merging and exit, then the HW_ID and XCC_ID registers and the workgroup id.
-__device__ __forceinline__ void stamp(const Args& a, int g, int slot) {
+__device__ __forceinline__ void stamp(const DecodeArgs& a, int g, int slot) {
     if (a.cta_clock && threadIdx.x == 0) {
         a.cta_clock[8 * g + slot] = wall_clock64();
         if (slot == 0) {

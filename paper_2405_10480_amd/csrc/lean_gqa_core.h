@@ -135,10 +135,7 @@ struct GqaCore {
         __device__ const float* o_at(int stream, int row, int col) const { return &area[stream].o[row][col]; }
     };
 
-    // `under_first_loads` is called once, right after the first K/V loads are issued: scalar work
-    // the caller wants done while they are in flight (it may fill in sg.first_cta / last_cta).
-    template <class Deferred>
-    __device__ static void run(const Args& a, const Segment& sg, Deferred&& under_first_loads, Smem& sm, int cta) {
+    __device__ static void run(const DecodeArgs& a, const Segment& sg, Smem& sm, int cta) {
         const int lane = threadIdx.x & 63;
         const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int r = lane & 15;   // A row / B column index of the lane
@@ -324,7 +321,6 @@ struct GqaCore {
             int k = 0;
             load_tile(k_slab, kA, off_at(0));
             load_tile(v_slab, vA, off_at(0));
-            under_first_loads();
             while (k < n_it) {
                 load_tile(k_slab, kB, off_at(k + 1));
                 load_tile(v_slab, vB, off_at(k + 1));
@@ -343,15 +339,12 @@ struct GqaCore {
             if constexpr (!kPipelined) {
                 // One register buffer: a wave issues one step's loads, consumes them, then issues
                 // the next; the other waves of the compute unit cover its memory latency.
-                load_tile(k_slab, kA, off_at(0));
-                load_tile(v_slab, vA, off_at(0));
-                under_first_loads();
                 for (int k = 0; k < n_it; ++k) {
+                    load_tile(k_slab, kA, off_at(k));
+                    load_tile(v_slab, vA, off_at(k));
                     stage_k(kA);
                     attend(vA, it_first + k);
                     if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
-                    load_tile(k_slab, kA, off_at(k + 1));
-                    load_tile(v_slab, vA, off_at(k + 1));
                 }
             } else {
                 // One register buffer, software-pipelined: the K registers are free as soon as the
@@ -360,7 +353,6 @@ struct GqaCore {
                 // the next step's scores and softmax.
                 load_tile(k_slab, kA, off_at(0));
                 load_tile(v_slab, vA, off_at(0));
-                under_first_loads();
                 for (int k = 0; k < n_it; ++k) {
                     stage_k(kA);
                     load_tile(k_slab, kA, off_at(k + 1));

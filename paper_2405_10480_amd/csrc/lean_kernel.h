@@ -23,7 +23,7 @@ struct OwnPartial {
 // re-scaling operator of Section 4.1, in ascending CTA order.  All loads of a batch are
 // issued before the first use, so one memory round trip covers the whole batch.
 template <int CPT, int THREADS, int D, int F>
-__device__ __forceinline__ void merge_children(const Args& a, OwnPartial<CPT>& own, int first, int step,
+__device__ __forceinline__ void merge_children(const DecodeArgs& a, OwnPartial<CPT>& own, int first, int step,
                                                int nchild, int n_chunks, int n_elem, int T_m) {
     const int tid = threadIdx.x;
     const buffer_rsrc ws = make_slab((const uint16_t*)a.partials, (uint32_t)a.sched.grid * (uint32_t)a.slot * 4u);
@@ -71,7 +71,7 @@ struct WideMergeScratch {
 };
 
 template <int THREADS, int D>
-__device__ __forceinline__ void merge_children_wide(const Args& a, OwnPartial<1>& own, int first, int step,
+__device__ __forceinline__ void merge_children_wide(const DecodeArgs& a, OwnPartial<1>& own, int first, int step,
                                                     int nchild, WideMergeScratch<THREADS>& sh) {
     constexpr int NCH = D / 4;
     constexpr int SLOTS = THREADS / NCH;
@@ -141,7 +141,7 @@ template <class Core>
 constexpr int kWideThreads = Core::kTmMax == 1 ? Core::kThreads : 1;
 
 template <class Core, int CPT, int F>
-__device__ __forceinline__ void reduce_tile(const Args& a, OwnPartial<CPT>& own, int g, int b, int h,
+__device__ __forceinline__ void reduce_tile(const DecodeArgs& a, OwnPartial<CPT>& own, int g, int b, int h,
                                             int first_cta, int last_cta,
                                             WideMergeScratch<kWideThreads<Core>>& wide_scratch) {
     constexpr int D = Core::kD;
@@ -222,7 +222,7 @@ __device__ __forceinline__ void reduce_tile(const Args& a, OwnPartial<CPT>& own,
 }
 
 template <class Core>
-__device__ __forceinline__ void lean_decode_body(const DecodeArgs& block) {
+__device__ __forceinline__ void lean_decode_body(const DecodeArgs& a) {
     constexpr int D = Core::kD;
     constexpr int THREADS = Core::kThreads;
     constexpr int CPT = (Core::kTmMax * D / 4 + THREADS - 1) / THREADS;  // float4 chunks per thread
@@ -236,11 +236,17 @@ __device__ __forceinline__ void lean_decode_body(const DecodeArgs& block) {
     __shared__ float parked_l[CPT * THREADS];
     __shared__ WideMergeScratch<kWideThreads<Core>> wide_scratch;  // (a 24-byte stub for the MFMA cores)
 
-    // The scalars become register values in one batch of loads; the first entries of the prefix
-    // tables are touched too, so that the table look-ups of small batches hit the scalar cache.
-    Args a(block);
-    pin_scalars(a);
-    asm volatile("" ::"s"(a.table.cu_iters[1]), "s"(a.table.cu_tok[1]));
+    // Touch every cache line of the argument block now, in one batch: left to itself the compiler
+    // loads each field right before its first use, and the span walk below becomes a chain of
+    // dependent misses to the argument segment (measured: 1.5-1.8 us before the first K/V load
+    // is issued).  One field per 64-byte line is enough (later reads hit the scalar cache) and
+    // keeps the scalar registers free; the first entries of the prefix tables are touched too,
+    // so that the table look-ups of small batches hit as well.
+    static_assert(offsetof(DecodeArgs, q) < 64 && offsetof(DecodeArgs, kv_seq_stride) / 64 == 1 &&
+                      offsetof(DecodeArgs, spin_limit) / 64 == 2 && offsetof(DecodeArgs, sched.iters_per_cta) / 64 == 3,
+                  "one touched field per line of the argument block");
+    asm volatile("" ::"s"(a.q), "s"(a.kv_seq_stride), "s"(a.spin_limit), "s"(a.sched.iters_per_cta),
+                 "s"(a.table.cu_iters[1]), "s"(a.table.cu_tok[1]));
 
     // CTA id.  The hardware deals consecutive workgroup ids round-robin to the
     // 8 XCDs; the optional remap makes the spans of one XCD contiguous so that
@@ -277,10 +283,7 @@ __device__ __forceinline__ void lean_decode_body(const DecodeArgs& block) {
     int64_t it = cta_start;
     Segment sg;
     while (it < cta_end) {
-        // Only where the segment starts is known here; which blocks share its tile (two divisions)
-        // is worked out by the core while its first K/V loads are in flight.
-        sg = it == cta_start ? locate_start(a.sched, a.table, it, cta_end)
-                             : locate_next_start(a.sched, a.table, sg, cta_end);
+        sg = it == cta_start ? locate(a.sched, a.table, it, cta_end) : locate_next(a.sched, a.table, sg, g, cta_end);
         if (it == cta_start) stamp(a, g, 2);
         if (a.ragged_q && tile_rows(a, sg.b, sg.h).count <= 0) {
             // a sequence with fewer query tokens than the longest: this row block holds no rows.
@@ -288,7 +291,7 @@ __device__ __forceinline__ void lean_decode_body(const DecodeArgs& block) {
             it = sg.tile_iter_end;
             continue;
         }
-        Core::run(a, sg, [&] { locate_peers(a.sched, sg, g); }, sm, g);  // ends with a workgroup barrier
+        Core::run(a, sg, sm, g);  // ends with a workgroup barrier
 
         // Fold the per-wave partial streams into the workgroup's partial.
         OwnPartial<CPT> own;

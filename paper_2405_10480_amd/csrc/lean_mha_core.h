@@ -45,10 +45,7 @@ struct MhaCore {
     // Computes this workgroup's share of one output tile: LeanTile iterations
     // [sg.local_iter, sg.local_iter_end) of (sg.b, sg.h).  Leaves one un-scaled
     // partial (O~, m, l) per wave in `sm` (base-2 log domain) and ends with a barrier.
-    // `under_first_loads` is called once, right after the first K/V loads are issued: scalar work
-    // the caller wants done while they are in flight (it may fill in sg.first_cta / last_cta).
-    template <class Deferred>
-    __device__ static void run(const Args& a, const Segment& sg, Deferred&& under_first_loads, Smem& sm, int cta) {
+    __device__ static void run(const DecodeArgs& a, const Segment& sg, Smem& sm, int cta) {
         const int lane = threadIdx.x & 63;
         const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int r = lane / kLPR;
@@ -149,7 +146,6 @@ struct MhaCore {
             int k = 0;
             load_tile(k_slab, kA, off_at(0));
             load_tile(v_slab, vA, off_at(0));
-            under_first_loads();
             while (k < n_it) {
                 load_tile(k_slab, kB, off_at(k + 1));
                 load_tile(v_slab, vB, off_at(k + 1));
@@ -169,15 +165,12 @@ struct MhaCore {
             // next; the other waves of the compute unit cover its memory latency.  (Issuing the
             // next K loads right after the dot products was tried: 2 % slower, the memory system
             // likes about 8 KiB in flight per wave best.)
-            load_tile(k_slab, kA, off_at(0));
-            load_tile(v_slab, vA, off_at(0));
-            under_first_loads();
             for (int k = 0; k < n_it; ++k) {
+                load_tile(k_slab, kA, off_at(k));
+                load_tile(v_slab, vA, off_at(k));
                 scores(kA, s);
                 attend(s, vA, it_first + k);
                 if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
-                load_tile(k_slab, kA, off_at(k + 1));
-                load_tile(v_slab, vA, off_at(k + 1));
             }
         }
 

@@ -57,7 +57,6 @@ struct Segment {
     int32_t local_iter;       // first LeanTile iteration inside the tile
     int32_t local_iter_end;   // one past the last
     int32_t n_ctx;            // N_b
-    int32_t c_n;              // LeanTile iterations of the tile, ceil(N_b / T_n)
     int32_t host;             // this CTA computed the tile's first iteration
     int32_t finishing;        // this CTA's span reaches the tile's end
     int32_t first_cta;        // CTA that computed the tile's first iteration (the host block)
@@ -90,67 +89,51 @@ LEAN_HD int find_sequence(const SchedTable& t, int B, int32_t key) {
     return lo;
 }
 
-// Where the segment of the tile containing global iteration `it` starts and ends inside the
-// span of a CTA that ends at cta_end: everything a block needs to address its first K/V rows.
-// first_cta / last_cta are left to locate_peers, whose divisions can then run while the first
-// loads are in flight.
-LEAN_HD Segment locate_start(const Sched& s, const SchedTable& t, int64_t it, int64_t cta_end) {
+// Segment of the tile containing global iteration `it`, clipped to the CTA's span end.
+LEAN_HD Segment locate(const Sched& s, const SchedTable& t, int64_t it, int64_t cta_end) {
     Segment sg;
     int64_t tile_iter;  // global index of the tile's first iteration
+    int32_t c_n;
     if (s.packed) {
         const int64_t per_head = t.cu_iters[s.B];
         sg.h = (int32_t)div_iters(s, it, per_head);
         const int32_t key = (int32_t)(it - (int64_t)sg.h * per_head);
         sg.b = find_sequence(t, s.B, key);
-        sg.c_n = t.cu_iters[sg.b + 1] - t.cu_iters[sg.b];
+        c_n = t.cu_iters[sg.b + 1] - t.cu_iters[sg.b];
         tile_iter = (int64_t)sg.h * per_head + t.cu_iters[sg.b];
         sg.tile_idx = sg.h * s.B + sg.b;
     } else {
         const int32_t key = (int32_t)div_iters(s, it, s.Hkv);
         sg.b = find_sequence(t, s.B, key);
-        sg.c_n = t.cu_iters[sg.b + 1] - t.cu_iters[sg.b];
+        c_n = t.cu_iters[sg.b + 1] - t.cu_iters[sg.b];
         const int64_t seq_iter = (int64_t)s.Hkv * t.cu_iters[sg.b];
-        sg.h = (int32_t)div_iters(s, it - seq_iter, sg.c_n);
-        tile_iter = seq_iter + (int64_t)sg.h * sg.c_n;
+        sg.h = (int32_t)div_iters(s, it - seq_iter, c_n);
+        tile_iter = seq_iter + (int64_t)sg.h * c_n;
         sg.tile_idx = sg.b * s.Hkv + sg.h;
     }
     sg.n_ctx = t.cu_tok[sg.b + 1] - t.cu_tok[sg.b];
-    sg.tile_iter_end = tile_iter + sg.c_n;
+    sg.tile_iter_end = tile_iter + c_n;
     sg.local_iter = (int32_t)(it - tile_iter);
     const int64_t stop = sg.tile_iter_end < cta_end ? sg.tile_iter_end : cta_end;
     sg.local_iter_end = (int32_t)(stop - tile_iter);
     sg.host = it == tile_iter;
     sg.finishing = cta_end >= sg.tile_iter_end;
-    sg.first_cta = sg.last_cta = -1;
-    return sg;
-}
-
-// The blocks that share the segment's tile: the host block and the last contributor.  g is the
-// CTA the segment belongs to, which is the host block of a tile it starts and the last contributor
-// of a tile it finishes (no division then); g < 0: not known, both are computed.
-LEAN_HD void locate_peers(const Sched& s, Segment& sg, int g) {
     if (s.fixed_split) {
-        const int parts = sg.c_n < s.fixed_split ? sg.c_n : s.fixed_split;
+        const int parts = c_n < s.fixed_split ? c_n : s.fixed_split;
         sg.first_cta = sg.tile_idx * s.fixed_split;
         sg.last_cta = sg.first_cta + parts - 1;
     } else {
-        sg.first_cta = g >= 0 && sg.host ? g : cta_of_iter(s, sg.tile_iter_end - sg.c_n);
-        sg.last_cta = g >= 0 && sg.finishing ? g : cta_of_iter(s, sg.tile_iter_end - 1);
+        sg.first_cta = cta_of_iter(s, tile_iter);
+        sg.last_cta = cta_of_iter(s, sg.tile_iter_end - 1);
     }
-}
-
-// Segment of the tile containing global iteration `it`, clipped to the CTA's span end.
-LEAN_HD Segment locate(const Sched& s, const SchedTable& t, int64_t it, int64_t cta_end) {
-    Segment sg = locate_start(s, t, it, cta_end);
-    locate_peers(s, sg, -1);
     return sg;
 }
 
-// The segment after `prev` in a CTA's span (stream-K spans; prev.tile_iter_end < cta_end):
+// The segment after `prev` in the span of CTA g (stream-K spans; prev.tile_iter_end < cta_end):
 // the next output tile in iteration order, from its first iteration, so this CTA is its host
-// block.  Same result as locate_start(s, t, prev.tile_iter_end, cta_end) without the searches
-// and divisions: the walk steps to the next head / next non-empty sequence.
-LEAN_HD Segment locate_next_start(const Sched& s, const SchedTable& t, const Segment& prev, int64_t cta_end) {
+// block.  Same result as locate(s, t, prev.tile_iter_end, cta_end) without the searches and
+// divisions: the walk steps to the next head / next non-empty sequence.
+LEAN_HD Segment locate_next(const Sched& s, const SchedTable& t, const Segment& prev, int g, int64_t cta_end) {
     Segment sg;
     sg.b = prev.b;
     sg.h = prev.h;
@@ -169,23 +152,17 @@ LEAN_HD Segment locate_next_start(const Sched& s, const SchedTable& t, const Seg
         }
         sg.tile_idx = sg.b * s.Hkv + sg.h;
     }
-    sg.c_n = t.cu_iters[sg.b + 1] - t.cu_iters[sg.b];
+    const int32_t c_n = t.cu_iters[sg.b + 1] - t.cu_iters[sg.b];
     const int64_t tile_iter = prev.tile_iter_end;
     sg.n_ctx = t.cu_tok[sg.b + 1] - t.cu_tok[sg.b];
-    sg.tile_iter_end = tile_iter + sg.c_n;
+    sg.tile_iter_end = tile_iter + c_n;
     sg.local_iter = 0;
     const int64_t stop = sg.tile_iter_end < cta_end ? sg.tile_iter_end : cta_end;
     sg.local_iter_end = (int32_t)(stop - tile_iter);
     sg.host = 1;
     sg.finishing = cta_end >= sg.tile_iter_end;
-    sg.first_cta = sg.last_cta = -1;
-    return sg;
-}
-
-// ... with its peers, for CTA g.
-LEAN_HD Segment locate_next(const Sched& s, const SchedTable& t, const Segment& prev, int g, int64_t cta_end) {
-    Segment sg = locate_next_start(s, t, prev, cta_end);
-    locate_peers(s, sg, g);
+    sg.first_cta = g;
+    sg.last_cta = sg.finishing ? g : cta_of_iter(s, sg.tile_iter_end - 1);
     return sg;
 }
 
