@@ -75,6 +75,24 @@ def _mk(B, Hq, Hkv, D, dtype, seqlens, layout, seed, outlier=0.0):
     return workloads.generate(w, device="cuda")
 
 
+def test_longest_context_a_slab_can_hold():
+    # One K/V slab is addressed through a buffer descriptor with 32-bit byte offsets: N_b * D * 2
+    # bytes must stay below 2^31.  The longest context at D = 64, one KV head (2 GiB of K, 2 GiB
+    # of V), through the single-row kernel and, with four query heads, the MFMA kernel.
+    D = 64
+    n_max = (2**31 - 1) // (D * 2)
+    for Hq in (1, 4):
+        inp = _mk(1, Hq, 1, D, "f16", [n_max], workloads.KV_PADDED, seed=90 + Hq, outlier=0.001)
+        want, want_lse = _oracle(inp)
+        got, got_lse, _ = _run(inp)
+        _check(got, got_lse, want, want_lse, f"N={n_max} Hq={Hq}")
+        del inp
+        torch.cuda.empty_cache()
+    with pytest.raises(la.LeanAttnError) as e:
+        la.lean_attn_schedule([n_max + 1], 1, 1, D, la.F16, la.KV_PADDED)
+    assert e.value.status == la.binding.ERR_SEQLEN
+
+
 # ------------------------------------------------------------------ small shapes, all variants
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("D", [64, 128, 256])
