@@ -16,6 +16,15 @@
  * (O~, m, l) triples are merged with the softmax re-scaling operator of
  * Section 4.1 inside the same launch (Algorithm 2).
  *
+ * One deliberate difference from Algorithm 2: there the host block (the CTA
+ * that computed a tile's first LeanTile) merges every peer in a flat loop.
+ * Here the CTAs of a tile form a reduction tree (fan-in lean_attn_tuning.
+ * merge_fanin) rooted at the FINISHING block, the CTA whose span holds the
+ * tile's last LeanTile: it merges last and writes the output.  The operator
+ * is associative (Section 4.1), so the result is the same; a CTA then only
+ * waits for lower CTA ids.  "host_block" in lean_attn_walk keeps Algorithm 2's
+ * meaning (first LeanTile of the tile), it no longer says who reduces.
+ *
  * All pointers named "device" are HIP device pointers on the current device;
  * "host" pointers are ordinary host memory.  No function takes ownership of
  * any buffer and no function allocates device memory.  Calls are asynchronous
@@ -160,15 +169,27 @@ typedef struct lean_attn_problem {
 } lean_attn_problem;
 
 /*
- * Bytes of device workspace lean_attn_decode needs for this problem shape:
- * arrival flags plus one partial (O~[T_m, D], m[T_m], l[T_m]) slot per CTA, as
- * in Algorithm 2 ("Op[g], mp[g], lp[g], flags[g]").  Host-only arithmetic; it
- * does not depend on the device.  Returns 0 for an unsupported shape.
+ * Bytes of device workspace that suffice for lean_attn_decode on this problem
+ * shape whatever the tuning: arrival flags plus one partial (O~[T_m, D], m[T_m],
+ * l[T_m]) slot per CTA, as in Algorithm 2 ("Op[g], mp[g], lp[g], flags[g]"),
+ * for LEAN_ATTN_MAX_GRID CTAs.  Host-only arithmetic; it does not depend on
+ * the device.  Returns 0 for an unsupported shape.
  */
 size_t lean_attn_workspace_size(int B, int Hq, int Hkv, int D, int dtype);
 
 /* The same for the problem lean_attn_attend is given.  Returns 0 for an unsupported problem. */
 size_t lean_attn_problem_workspace_size(const lean_attn_problem* problem);
+
+/*
+ * The workspace for launches of at most `max_grid` workgroups (1..LEAN_ATTN_MAX_GRID): a launch
+ * needs the flags plus `grid` partial slots, and every entry point checks exactly that against
+ * workspace_bytes (LEAN_ATTN_ERR_WORKSPACE otherwise, nothing launched).  The default grid is
+ * compute units x 1, or x 2 for batches of many short contexts (lean_attn_plan.grid tells), so a
+ * caller that never forces a larger grid can allocate for 2 x the unit count instead of
+ * LEAN_ATTN_MAX_GRID (e.g. 8.5 MB instead of 68 MB for 32-row tiles at D = 128 on 256 units).
+ * Returns 0 for an unsupported problem or grid.
+ */
+size_t lean_attn_workspace_size_for_grid(const lean_attn_problem* problem, int max_grid);
 
 /*
  * Clear the flags of a freshly allocated workspace (device pointer, 256-byte

@@ -5,6 +5,6 @@ from .binding import (  # noqa: F401
     lean_attn_launch_block_size,
     lean_attn_decode, lean_attn_problem_schedule, lean_attn_problem_workspace_size, lean_attn_read_probe,
     lean_attn_schedule, lean_attn_strerror, lean_attn_walk, lean_attn_workspace_init,
-    lean_attn_workspace_size, lean_attn_workspace_status, library_path,
+    lean_attn_workspace_size, lean_attn_workspace_size_for_grid, lean_attn_workspace_status, library_path,
 )
 from .buildlib import build  # noqa: F401

@@ -102,6 +102,8 @@ def _load():
                                      ctypes.c_float, i32, ctypes.POINTER(Tuning), vp]
     lib.lean_attn_problem_workspace_size.restype = sz
     lib.lean_attn_problem_workspace_size.argtypes = [ctypes.POINTER(Problem)]
+    lib.lean_attn_workspace_size_for_grid.restype = sz
+    lib.lean_attn_workspace_size_for_grid.argtypes = [ctypes.POINTER(Problem), i32]
     lib.lean_attn_problem_schedule.restype = i32
     lib.lean_attn_problem_schedule.argtypes = [ctypes.POINTER(Problem), vp, ctypes.POINTER(Tuning),
                                                ctypes.POINTER(Plan)]
@@ -257,6 +259,10 @@ def lean_attn_decode(q, k_cache, v_cache, seqlens, out, workspace, *, Hkv: int, 
 
 def lean_attn_problem_workspace_size(problem: Problem) -> int:
     return int(_load().lean_attn_problem_workspace_size(ctypes.byref(problem)))
+
+
+def lean_attn_workspace_size_for_grid(problem: Problem, max_grid: int) -> int:
+    return int(_load().lean_attn_workspace_size_for_grid(ctypes.byref(problem), int(max_grid)))
 
 
 def lean_attn_problem_schedule(problem: Problem, seqlens, tuning: Optional[Tuning] = None) -> Plan:

@@ -97,6 +97,11 @@ static int dim_index(int D) { return D == 64 ? 0 : D == 128 ? 1 : D == 256 ? 2 :
 // Most query rows one output tile can hold: two MFMA row blocks up to D = 128, one at D = 256.
 static int max_tile_rows(int D) { return D <= 128 ? LEAN_ATTN_MAX_TILE_ROWS : 16; }
 
+// Workspace bytes a launch of `grid` workgroups with T_m-row partials touches.
+static size_t workspace_need(int64_t grid, int T_m, int D) {
+    return kPartialsOffset + (size_t)grid * slot_floats(T_m, D) * sizeof(float);
+}
+
 // kernel: 0 VALU single-row core, 1 MFMA query-group core; T_m: query rows per output tile
 static bool pick_variant(int kernel, int dtype, int D, int shape, int T_m, Variant* v) {
     if (shape < 0 || shape >= kNumShapes || dim_index(D) < 0 || T_m < 1 || T_m > max_tile_rows(D)) return false;
@@ -343,9 +348,23 @@ using namespace lean;
 
 extern "C" {
 
+// Rows per partial slot the launches of `p` can need.  A batch beyond one launch with per-sequence
+// query lengths runs chunk by chunk, each chunk cut into row blocks by ITS longest query: a chunk
+// can then hold more rows per tile than the whole problem would (33 rows make two blocks of 17,
+// 32 rows one block of 32), so such problems are sized for the largest tile.
+static int slot_rows(const lean_attn_problem& p) {
+    if (p.q_lens && p.B > LEAN_ATTN_MAX_BATCH) return max_tile_rows(p.D);
+    return row_blocks(p).T_m;
+}
+
+size_t lean_attn_workspace_size_for_grid(const lean_attn_problem* problem, int max_grid) {
+    if (!problem || check_problem(*problem, true) != LEAN_ATTN_OK) return 0;
+    if (max_grid < 1 || max_grid > LEAN_ATTN_MAX_GRID) return 0;
+    return workspace_need(max_grid, slot_rows(*problem), problem->D);
+}
+
 size_t lean_attn_problem_workspace_size(const lean_attn_problem* problem) {
-    if (!problem || check_problem(*problem, true) != LEAN_ATTN_OK) return 0;  // the size does not depend on B
-    return kPartialsOffset + (size_t)kMaxGrid * slot_floats(row_blocks(*problem).T_m, problem->D) * sizeof(float);
+    return lean_attn_workspace_size_for_grid(problem, LEAN_ATTN_MAX_GRID);
 }
 
 size_t lean_attn_workspace_size(int B, int Hq, int Hkv, int D, int dtype) {
@@ -514,15 +533,22 @@ static int build_launch(const lean_attn_problem& p, const void* q, const void* k
     return LEAN_ATTN_OK;
 }
 
+// One launch of at most LEAN_ATTN_MAX_BATCH sequences.  With `dry` every check runs (schedule, kernel
+// variant, workspace need) and nothing is launched.
 static int launch_one(const lean_attn_problem& p, const void* q, const void* k_cache, const void* v_cache,
-                      const int32_t* seqlens, void* out, float* lse, void* workspace, const lean_attn_tuning* tuning,
-                      hipStream_t stream, int64_t tok_base, int64_t tok_total) {
+                      const int32_t* seqlens, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                      const lean_attn_tuning* tuning, hipStream_t stream, int64_t tok_base, int64_t tok_total,
+                      bool dry, int max_grid) {
     lean_attn_plan plan;
     Variant var;
     DecodeArgs a;
     int rc = build_launch(p, q, k_cache, v_cache, seqlens, out, lse, workspace, tuning, tok_base, tok_total, false,
                           &plan, &var, &a);
     if (rc != LEAN_ATTN_OK) return rc;
+    // the partial stores of CTA g land at slot g: the slab of this launch must fit the caller's buffer
+    if (plan.grid > max_grid || workspace_need(plan.grid, plan.T_m, p.D) > workspace_bytes)
+        return LEAN_ATTN_ERR_WORKSPACE;
+    if (dry) return LEAN_ATTN_OK;
     if (plan.total_iters == 0) {  // every sequence is empty
         const int64_t rows = (int64_t)a.table.cu_q[p.B] * p.Hq;
         const int row_words = a.out16 ? p.D / 2 : p.D;
@@ -549,27 +575,13 @@ struct LaunchBlock {
 };
 constexpr uint64_t kBlockMagic = 0x314b4c424e41454cull;  // "LEANBLK1"
 
-int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void* k_cache, const void* v_cache,
-                     const int32_t* seqlens, void* out, float* lse, void* workspace, size_t workspace_bytes,
-                     const lean_attn_tuning* tuning, void* hip_stream) {
-    if (!problem || !q || !k_cache || !v_cache || !seqlens || !out || !workspace) return LEAN_ATTN_ERR_NULL_POINTER;
-    const lean_attn_problem& p = *problem;
-    int rc = check_problem(p, true);
-    if (rc != LEAN_ATTN_OK) return rc;
-    if ((((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15) != 0)
-        return LEAN_ATTN_ERR_BAD_SHAPE;
-    if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < lean_attn_problem_workspace_size(problem))
-        return LEAN_ATTN_ERR_WORKSPACE;
-    // every length is checked before the first launch: on error nothing runs
-    int64_t tok_total = 0;
-    rc = check_lengths(p, seqlens, &tok_total);
-    if (rc != LEAN_ATTN_OK) return rc;
-    hipStream_t stream = (hipStream_t)hip_stream;
-    if (p.B <= LEAN_ATTN_MAX_BATCH)
-        return launch_one(p, q, k_cache, v_cache, seqlens, out, lse, workspace, tuning, stream, 0, tok_total);
-
-    // A larger batch: consecutive launches of at most LEAN_ATTN_MAX_BATCH sequences on the same
-    // stream (the schedule table of one launch travels in its kernel arguments) sharing the workspace.
+// The launches of a batch beyond LEAN_ATTN_MAX_BATCH: consecutive chunks of at most that many
+// sequences on the same stream (the schedule table of one launch travels in its kernel
+// arguments), sharing the workspace.  With `dry` every chunk is checked and nothing is launched.
+static int launch_chunks(const lean_attn_problem& p, const void* q, const void* k_cache, const void* v_cache,
+                         const int32_t* seqlens, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                         const lean_attn_tuning* tuning, hipStream_t stream, int64_t tok_total, bool dry,
+                         int max_grid) {
     const size_t out_elem = p.out_dtype == LEAN_ATTN_OUT_AS_INPUT ? 2 : 4;
     int64_t tok_base = 0, row_base = 0;  // tokens / (query token, head) rows before the chunk
     for (int b0 = 0; b0 < p.B; b0 += LEAN_ATTN_MAX_BATCH) {
@@ -595,16 +607,50 @@ int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void
                 kc += skip;
                 vc += skip;
             }
-            rc = launch_one(c, (const char*)q + (size_t)row_base * p.D * 2, kc, vc, seqlens + b0,
-                            (char*)out + (size_t)row_base * p.D * out_elem, lse ? lse + row_base : nullptr, workspace,
-                            tuning, stream, p.kv_layout == LEAN_ATTN_KV_PACKED ? tok_base : 0,
-                            p.kv_layout == LEAN_ATTN_KV_PACKED ? tok_total : chunk_toks);
+            const int rc = launch_one(c, (const char*)q + (size_t)row_base * p.D * 2, kc, vc, seqlens + b0,
+                                      (char*)out + (size_t)row_base * p.D * out_elem, lse ? lse + row_base : nullptr,
+                                      workspace, workspace_bytes, tuning, stream,
+                                      p.kv_layout == LEAN_ATTN_KV_PACKED ? tok_base : 0,
+                                      p.kv_layout == LEAN_ATTN_KV_PACKED ? tok_total : chunk_toks, dry, max_grid);
             if (rc != LEAN_ATTN_OK) return rc;
         }
         tok_base += chunk_toks;
         row_base += chunk_q * p.Hq;
     }
     return LEAN_ATTN_OK;
+}
+
+// lean_attn_attend on a workspace the caller or the library provides.
+static int attend_on(const lean_attn_problem* problem, const void* q, const void* k_cache, const void* v_cache,
+                     const int32_t* seqlens, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                     const lean_attn_tuning* tuning, void* hip_stream, bool dry = false,
+                     int max_grid = LEAN_ATTN_MAX_GRID) {
+    if (!problem || !q || !k_cache || !v_cache || !seqlens || !out || !workspace) return LEAN_ATTN_ERR_NULL_POINTER;
+    const lean_attn_problem& p = *problem;
+    int rc = check_problem(p, true);
+    if (rc != LEAN_ATTN_OK) return rc;
+    if ((((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15) != 0)
+        return LEAN_ATTN_ERR_BAD_SHAPE;
+    if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < kPartialsOffset) return LEAN_ATTN_ERR_WORKSPACE;
+    // every length and every launch is checked before the first launch: on error nothing runs
+    int64_t tok_total = 0;
+    rc = check_lengths(p, seqlens, &tok_total);
+    if (rc != LEAN_ATTN_OK) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (p.B <= LEAN_ATTN_MAX_BATCH)
+        return launch_one(p, q, k_cache, v_cache, seqlens, out, lse, workspace, workspace_bytes, tuning, stream, 0,
+                          tok_total, dry, max_grid);
+    rc = launch_chunks(p, q, k_cache, v_cache, seqlens, out, lse, workspace, workspace_bytes, tuning, stream,
+                       tok_total, true, max_grid);
+    if (rc != LEAN_ATTN_OK || dry) return rc;
+    return launch_chunks(p, q, k_cache, v_cache, seqlens, out, lse, workspace, workspace_bytes, tuning, stream,
+                         tok_total, false, max_grid);
+}
+
+int lean_attn_attend(const lean_attn_problem* problem, const void* q, const void* k_cache, const void* v_cache,
+                     const int32_t* seqlens, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                     const lean_attn_tuning* tuning, void* hip_stream) {
+    return attend_on(problem, q, k_cache, v_cache, seqlens, out, lse, workspace, workspace_bytes, tuning, hip_stream);
 }
 
 size_t lean_attn_launch_block_size(void) { return sizeof(LaunchBlock); }
@@ -619,8 +665,7 @@ int lean_attn_attend_prepare(const lean_attn_problem* problem, const void* q, co
     if (rc != LEAN_ATTN_OK) return rc;
     if ((((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out | (uintptr_t)block_host) & 15) != 0)
         return LEAN_ATTN_ERR_BAD_SHAPE;
-    if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < lean_attn_problem_workspace_size(problem))
-        return LEAN_ATTN_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < kPartialsOffset) return LEAN_ATTN_ERR_WORKSPACE;
     if (tuning && (tuning->fixed_split != 0 || tuning->tile_shape != 0)) return LEAN_ATTN_ERR_TUNING;
     int64_t tok_total = 0;
     rc = check_lengths(p, seqlens, &tok_total);
@@ -631,6 +676,7 @@ int lean_attn_attend_prepare(const lean_attn_problem* problem, const void* q, co
     rc = build_launch(p, q, k_cache, v_cache, seqlens, out, lse, workspace, tuning, 0, tok_total, true, &plan, &var,
                       &blk.args);
     if (rc != LEAN_ATTN_OK) return rc;
+    if (workspace_need(plan.grid, plan.T_m, p.D) > workspace_bytes) return LEAN_ATTN_ERR_WORKSPACE;
     if (!var.fn_indirect) return LEAN_ATTN_ERR_UNSUPPORTED;
     blk.magic = kBlockMagic;
     blk.fn = var.fn_indirect;
@@ -684,8 +730,8 @@ const char* lean_attn_strerror(int status) {
         case LEAN_ATTN_OK: return "ok";
         case LEAN_ATTN_ERR_NULL_POINTER: return "a required pointer is null";
         case LEAN_ATTN_ERR_BAD_SHAPE: return "bad shape: B, N_q, Hq, Hkv must be positive, Hq a multiple of Hkv, at most 256 query rows per KV head, 16-byte aligned tensors";
-        case LEAN_ATTN_ERR_UNSUPPORTED: return "unsupported head dim (64, 128), dtype (f16, bf16) or layout";
-        case LEAN_ATTN_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or smaller than lean_attn_workspace_size";
+        case LEAN_ATTN_ERR_UNSUPPORTED: return "unsupported head dim (64, 128, 256), dtype (f16, bf16), output type or layout";
+        case LEAN_ATTN_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or too small for the flags and one partial slot per workgroup of the launch";
         case LEAN_ATTN_ERR_SEQLEN: return "negative sequence length, padded stride below the longest sequence, or more than 2^31 tokens";
         case LEAN_ATTN_ERR_BATCH_TOO_LARGE: return "batch larger than LEAN_ATTN_MAX_BATCH";
         case LEAN_ATTN_ERR_HIP: return "a HIP runtime call failed";

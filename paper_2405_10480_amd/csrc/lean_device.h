@@ -40,7 +40,7 @@ struct DecodeArgs {
     int32_t ragged_q;      // per-sequence query lengths: q, out, lse are packed by table.cu_q
     int32_t group;         // Hq / Hkv
     int32_t rows;          // N_q * group query rows share one KV head; row rho = token*group + head
-    int32_t C_m;           // row blocks per KV head, ceil(rows / 16)
+    int32_t C_m;           // row blocks per KV head, ceil(rows / 32) (ceil(rows / 16) at D = 256)
     int32_t T_m;           // rows per block, ceil(rows / C_m); the last block may hold fewer
     int32_t causal;        // row of query token i sees the first N_b - N_q + i + 1 cached tokens
     int32_t out16;         // out holds 16-bit elements

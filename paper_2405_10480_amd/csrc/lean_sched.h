@@ -3,8 +3,8 @@
 // that both run literally the same index arithmetic.
 //
 // Output tile  = one (sequence b, head h) pair; it owns C_n[b] = ceil(N_b / T_n)
-//                LeanTile iterations.  With up to 16 query rows per KV head, h is the KV
-//                head; with more, the rows are cut into C_m blocks and h = kv_head*C_m + block
+//                LeanTile iterations.  With up to 32 query rows per KV head (16 at D = 256), h is
+//                the KV head; with more, the rows are cut into C_m blocks and h = kv_head*C_m + block
 //                (Algorithm 2's C_m output tiles along the query dimension).
 // Linearization: PADDED cache  b -> h -> context   (iter = Hkv*cuC[b] + h*C_n[b] + local)
 //                PACKED cache  h -> b -> context   (iter = h*cuC[B] + cuC[b] + local)

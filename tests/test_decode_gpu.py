@@ -180,6 +180,64 @@ def test_error_paths_launch_nothing():
     assert torch.all(out == 0)
 
 
+def test_workspace_sized_for_the_launch_grid_and_checked_per_launch():
+    # the flags plus one partial slot per workgroup of the launch is all a call needs; one slot less is
+    # an error and nothing is launched
+    inp = _mk(1, 16, 2, 128, "bf16", [40000], workloads.KV_PADDED, seed=5)
+    w = inp.w
+    want, want_lse = _oracle(inp)
+    pr = la.Problem(B=1, N_q=1, Hq=16, Hkv=2, D=128, dtype=la.BF16, out_dtype=la.OUT_F32, kv_layout=la.KV_PADDED,
+                    causal=0, scale=w.scale, kv_seq_stride=w.n_stride)
+    for tn in (None, la.Tuning(grid=700)):
+        grid = la.lean_attn_problem_schedule(pr, inp.seqlens, tn).grid
+        assert grid > 8
+        ws = torch.empty(la.lean_attn_workspace_size_for_grid(pr, grid), dtype=torch.uint8, device="cuda")
+        la.lean_attn_workspace_init(ws)
+        got, got_lse, _ = _run(inp, tuning=tn, ws=ws)
+        _check(got, got_lse, want, want_lse, f"workspace for grid {grid}")
+        small = torch.empty(la.lean_attn_workspace_size_for_grid(pr, grid - 1), dtype=torch.uint8, device="cuda")
+        la.lean_attn_workspace_init(small)
+        out = torch.full((1, 16, 128), 7.0, dtype=torch.float32, device="cuda")
+        with pytest.raises(la.LeanAttnError) as e:
+            la.lean_attn_decode(inp.q, inp.k, inp.v, inp.seqlens, out, small, Hkv=2, kv_seq_stride=w.n_stride,
+                                scale=w.scale, tuning=tn)
+        torch.cuda.synchronize()
+        assert e.value.status == la.binding.ERR_WORKSPACE and torch.all(out == 7.0)
+
+
+def test_chunked_batch_with_query_lengths_and_a_forced_grid_stays_inside_the_workspace():
+    # 300 sequences run as two launches.  The whole problem has 33 rows per KV head (two blocks of 17),
+    # the second chunk only 32 (one block of 32 rows: larger partial slots); with a forced grid of 4096
+    # the partial slab of that chunk must still fit the workspace the size query gave.
+    r = np.random.default_rng(11)
+    B, Hkv, group, D = 300, 1, 11, 64
+    q_lens = [int(x) for x in r.integers(0, 3, size=B)]
+    q_lens[3] = 3                                   # 33 rows in the first chunk
+    q_lens[256:] = [int(x) for x in r.integers(0, 3, size=B - 256)]
+    q_lens[299] = 2
+    assert max(q_lens[256:]) == 2 and max(q_lens) == 3
+    seqlens = [max(int(x), q) for x, q in zip(r.integers(0, 40, size=B), q_lens)]
+    seqlens[7], seqlens[280] = 30000, 30000         # enough LeanTile iterations for a grid of 4096
+    w = workloads.Workload("chunked_forced_grid", B, Hkv * group, Hkv, D, "bf16", tuple(seqlens), workloads.KV_PACKED,
+                           seed=36, N_q=3, causal=True, q_lens=tuple(q_lens))
+    inp = workloads.generate(w, device="cuda")
+    pr = _problem_of(w).set_q_lens(q_lens)
+    nbytes = la.lean_attn_problem_workspace_size(pr)
+    # guard bytes after the workspace: a store past its end would land there
+    buf = torch.zeros(nbytes + (1 << 20), dtype=torch.uint8, device="cuda")
+    ws = buf[:nbytes]
+    la.lean_attn_workspace_init(ws)
+    n_tok = int(sum(q_lens))
+    out = torch.full((n_tok, w.Hq, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((n_tok, w.Hq), float("nan"), dtype=torch.float32, device="cuda")
+    la.lean_attn_attend(pr, inp.q, inp.k, inp.v, inp.seqlens, out, ws, lse=lse, tuning=la.Tuning(grid=4096))
+    torch.cuda.synchronize()
+    assert la.lean_attn_workspace_status(ws) == 0
+    assert torch.all(buf[nbytes:] == 0), "a partial was stored past the end of the workspace"
+    want, want_lse = _oracle_ragged(inp)
+    _check(out.cpu().numpy(), lse.cpu().numpy(), want, want_lse, "chunked, forced grid")
+
+
 def test_all_sequences_empty():
     inp = _mk(2, 4, 2, 64, "f16", [0, 0], workloads.KV_PADDED, seed=1)
     # a padded cache needs at least one row of storage to have a valid pointer
@@ -519,8 +577,11 @@ def test_attend_error_paths():
     with pytest.raises(la.LeanAttnError) as e:       # causal with fewer cached tokens than query rows
         la.lean_attn_attend(pr, inp.q, inp.k, inp.v, [3], out, ws)
     assert e.value.status == la.binding.ERR_SEQLEN
-    with pytest.raises(la.LeanAttnError) as e:       # workspace sized for a smaller tile
-        small = torch.empty(la.lean_attn_workspace_size(1, 2, 2, 128, la.BF16), dtype=torch.uint8, device="cuda")
+    with pytest.raises(la.LeanAttnError) as e:       # workspace sized for a smaller tile on the same grid
+        grid = la.lean_attn_problem_schedule(pr, [100]).grid
+        one_row = la.Problem(B=1, N_q=1, Hq=2, Hkv=2, D=128, dtype=la.BF16, out_dtype=la.OUT_F32,
+                             kv_layout=la.KV_PADDED, causal=0, scale=1.0, kv_seq_stride=100)
+        small = torch.empty(la.lean_attn_workspace_size_for_grid(one_row, grid), dtype=torch.uint8, device="cuda")
         la.lean_attn_attend(pr, inp.q, inp.k, inp.v, [100], out, small)
     assert e.value.status == la.binding.ERR_WORKSPACE
     with pytest.raises(ValueError):                  # out dtype must match the problem

@@ -185,6 +185,26 @@ def test_span_invariants_with_row_blocks(layout, G):
     _check_invariants(seqlens, 4, layout, p)
 
 
+def test_workspace_size_grows_with_the_grid_and_with_the_tile_rows():
+    pr = _problem(1, 1, 64, 8, 128)                      # 8 rows per tile
+    full = la.lean_attn_problem_workspace_size(pr)
+    assert la.lean_attn_workspace_size_for_grid(pr, la.binding.MAX_GRID) == full
+    assert la.lean_attn_workspace_size(1, 64, 8, 128, la.BF16) == full
+    flags = 256 + 4 * la.binding.MAX_GRID
+    slot = -(-8 * (128 + 2) * 4 // 256) * 256            # (O~[8,128], m[8], l[8]) in fp32, rounded up to 256 bytes
+    for g in (1, 256, 512, 4096):
+        assert la.lean_attn_workspace_size_for_grid(pr, g) == flags + g * slot
+    assert la.lean_attn_workspace_size_for_grid(pr, 0) == 0
+    assert la.lean_attn_workspace_size_for_grid(pr, la.binding.MAX_GRID + 1) == 0
+    # 33 rows per KV head make two blocks of 17; beyond one launch with per-sequence query lengths a
+    # chunk may run one block of 32, so that case is sized for the largest tile
+    p33 = _problem(2, 3, 11, 1, 64)
+    p32 = _problem(2, 2, 16, 1, 64)
+    assert la.lean_attn_problem_workspace_size(p33) < la.lean_attn_problem_workspace_size(p32)
+    big = _problem(300, 3, 11, 1, 64).set_q_lens([3] * 300)
+    assert la.lean_attn_problem_workspace_size(big) == la.lean_attn_problem_workspace_size(p32)
+
+
 def test_problem_argument_errors():
     tn = la.Tuning(num_cus=4)
     def status(pr, seqlens):
