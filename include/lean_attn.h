@@ -53,7 +53,8 @@ typedef enum lean_attn_status {
     LEAN_ATTN_ERR_BATCH_TOO_LARGE = -6, /* B > LEAN_ATTN_MAX_BATCH in a schedule query */
     LEAN_ATTN_ERR_HIP = -7,           /* a HIP runtime call failed (no device, bad stream, ...) */
     LEAN_ATTN_ERR_TUNING = -8,        /* a lean_attn_tuning field is out of range */
-    LEAN_ATTN_ERR_PEER_TIMEOUT = -9   /* reported by lean_attn_workspace_status only */
+    LEAN_ATTN_ERR_PEER_TIMEOUT = -9,  /* reported by lean_attn_workspace_status only */
+    LEAN_ATTN_ERR_STATIC_LIMIT = -10  /* lean_attn_decode_static: the launch exceeds the static scratch */
 } lean_attn_status;
 
 /* Element type of q, k_cache and v_cache. */
@@ -79,6 +80,7 @@ typedef enum lean_attn_kv_layout { LEAN_ATTN_KV_PADDED = 0, LEAN_ATTN_KV_PACKED 
 #define LEAN_ATTN_MAX_TILE_ROWS 32    /* query rows of one output tile: two MFMA row blocks (one, 16 rows, at D = 256) */
 #define LEAN_ATTN_MAX_QUERY_ROWS 256  /* N_q * Hq / Hkv: query rows that share one KV head */
 #define LEAN_ATTN_MAX_GRID 4096  /* upper bound on workgroups; sizes the workspace */
+#define LEAN_ATTN_STATIC_MAX_GRID 512  /* workgroups per launch of lean_attn_decode_static */
 
 /*
  * The stream-K schedule of one call (Section 4.3 and the first lines of
@@ -258,6 +260,28 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache,
                      size_t workspace_bytes, int B, int Hq, int Hkv, int D, int kv_layout,
                      int64_t kv_seq_stride, float scale, int dtype, const lean_attn_tuning* tuning,
                      void* hip_stream);
+
+/*
+ * lean_attn_decode for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results as lean_attn_decode, without `workspace` / `workspace_bytes`: the
+ * flags and partial slots live in a static device array inside the library (8.5 MB per GPU, held
+ * until the process ends), enough for LEAN_ATTN_STATIC_MAX_GRID workgroups with the largest
+ * partial slot.  The default grid (compute units x 1 or x 2) fits on devices of up to 256 units;
+ * a launch that needs more slots (a larger device, tuning->grid, grid_multiple or fixed_split
+ * beyond the limit) returns LEAN_ATTN_ERR_STATIC_LIMIT and launches nothing.  No hipMalloc,
+ * hipFree or other allocating call is made.  The status word and flags are cleared by a small
+ * fill kernel at the start of every call.  All calls on one GPU share the one array: calls that
+ * overlap on a GPU (two streams, two threads) race; serialise them or use lean_attn_decode with
+ * a workspace per stream.  A peer time-out cannot be queried here (the output rows of the tile
+ * are then invalid, as for lean_attn_decode); it needs tuning->spin_limit set far below its
+ * default to happen on a healthy device.  The first call on a device reads the array's address,
+ * the device's unit count and the kernel's residency from the runtime: make it outside capture.
+ */
+int lean_attn_decode_static(const void* q, const void* k_cache, const void* v_cache,
+                            const int32_t* seqlens, float* out, float* lse, int B, int Hq, int Hkv,
+                            int D, int kv_layout, int64_t kv_seq_stride, float scale, int dtype,
+                            const lean_attn_tuning* tuning, void* hip_stream);
 
 /*
  * Attention of short query tiles over the KV cache (Algorithm 2 with C_m >= 1).

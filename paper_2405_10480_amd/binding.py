@@ -20,7 +20,8 @@ MAX_BATCH, MAX_TILE_ROWS, MAX_QUERY_ROWS, MAX_GRID = 256, 32, 256, 4096
 
 OK = 0
 ERR_NULL_POINTER, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE = -1, -2, -3, -4
-ERR_SEQLEN, ERR_BATCH_TOO_LARGE, ERR_HIP, ERR_TUNING, ERR_PEER_TIMEOUT = -5, -6, -7, -8, -9
+ERR_SEQLEN, ERR_BATCH_TOO_LARGE, ERR_HIP, ERR_TUNING, ERR_PEER_TIMEOUT, ERR_STATIC_LIMIT = -5, -6, -7, -8, -9, -10
+STATIC_MAX_GRID = 512
 
 
 class Plan(ctypes.Structure):
@@ -100,6 +101,9 @@ def _load():
     lib.lean_attn_decode.restype = i32
     lib.lean_attn_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i32, i32, i32, i32, i32, i64,
                                      ctypes.c_float, i32, ctypes.POINTER(Tuning), vp]
+    lib.lean_attn_decode_static.restype = i32
+    lib.lean_attn_decode_static.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i64,
+                                            ctypes.c_float, i32, ctypes.POINTER(Tuning), vp]
     lib.lean_attn_problem_workspace_size.restype = sz
     lib.lean_attn_problem_workspace_size.argtypes = [ctypes.POINTER(Problem)]
     lib.lean_attn_workspace_size_for_grid.restype = sz
@@ -225,9 +229,11 @@ def lean_attn_decode(q, k_cache, v_cache, seqlens, out, workspace, *, Hkv: int, 
                      stream=None, prepare_only: bool = False):
     """Launch decode attention on the current (or given) HIP stream.  Shapes as in ``lean_attn.h``.
 
-    With ``prepare_only`` nothing is launched and a :class:`PreparedCall` is returned instead."""
+    With ``prepare_only`` nothing is launched and a :class:`PreparedCall` is returned instead.
+    ``workspace=None`` calls ``lean_attn_decode_static`` (the library's static scratch)."""
     B, Hq, D = q.shape
-    if not (q.is_cuda and k_cache.is_cuda and v_cache.is_cuda and out.is_cuda and workspace.is_cuda):
+    if not (q.is_cuda and k_cache.is_cuda and v_cache.is_cuda and out.is_cuda and
+            (workspace is None or workspace.is_cuda)):
         raise ValueError("q, k_cache, v_cache, out and workspace must be device tensors")
     if not (q.is_contiguous() and k_cache.is_contiguous() and v_cache.is_contiguous() and out.is_contiguous()):
         raise ValueError("tensors must be contiguous")
@@ -246,13 +252,18 @@ def lean_attn_decode(q, k_cache, v_cache, seqlens, out, workspace, *, Hkv: int, 
     if lse is not None and (str(lse.dtype) != "torch.float32" or lse.numel() != B * Hq or not lse.is_cuda):
         raise ValueError("lse must be a float32 device tensor [B, Hq]")
     arr = _seqlens_array(seqlens)
-    args = (q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), arr, out.data_ptr(),
-            lse.data_ptr() if lse is not None else None, workspace.data_ptr(),
-            workspace.numel() * workspace.element_size(), B, Hq, Hkv, D, kv_layout, int(kv_seq_stride),
-            float(scale), _dtype_code(q), _tuning_ptr(tuning), _stream_handle(stream))
+    head = (q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), arr, out.data_ptr(),
+            lse.data_ptr() if lse is not None else None)
+    tail = (B, Hq, Hkv, D, kv_layout, int(kv_seq_stride), float(scale), _dtype_code(q), _tuning_ptr(tuning),
+            _stream_handle(stream))
+    if workspace is None:
+        fn, args = _load().lean_attn_decode_static, head + tail
+    else:
+        fn = _load().lean_attn_decode
+        args = head + (workspace.data_ptr(), workspace.numel() * workspace.element_size()) + tail
     if prepare_only:
-        return PreparedCall(_load().lean_attn_decode, args, (q, k_cache, v_cache, out, lse, workspace, arr, tuning))
-    rc = _load().lean_attn_decode(*args)
+        return PreparedCall(fn, args, (q, k_cache, v_cache, out, lse, workspace, arr, tuning))
+    rc = fn(*args)
     if rc != OK:
         raise LeanAttnError(rc)
 

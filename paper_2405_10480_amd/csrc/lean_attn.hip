@@ -715,6 +715,58 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache, co
                             hip_stream);
 }
 
+// ---- lean_attn_decode for callers that cannot allocate: the workspace is a static device array ----
+// Partial slots of the largest tile (32 rows at D = 128, 16 at D = 256) for LEAN_ATTN_STATIC_MAX_GRID
+// workgroups plus the flags: 8.5 MB, held by every GPU the library runs on until the process ends.
+constexpr size_t kStaticScratchBytes =
+    kPartialsOffset + (size_t)LEAN_ATTN_STATIC_MAX_GRID * 4160 * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+// In host code `scratch` is only a handle for the runtime's symbol look-up, never an address a
+// kernel may be given: the array's device address is read once per device and kept here.
+static void* g_scratch_ptr[64];
+static std::mutex g_scratch_mutex;
+
+static int static_scratch(void** ptr) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LEAN_ATTN_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {  // each device holds its own copy of the array at its own address
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return LEAN_ATTN_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return LEAN_ATTN_OK;
+}
+
+int lean_attn_decode_static(const void* q, const void* k_cache, const void* v_cache, const int32_t* seqlens,
+                            float* out, float* lse, int B, int Hq, int Hkv, int D, int kv_layout,
+                            int64_t kv_seq_stride, float scale, int dtype, const lean_attn_tuning* tuning,
+                            void* hip_stream) {
+    static_assert(slot_floats_max() <= 4160, "the static scratch holds the largest partial slot");
+    const lean_attn_problem p = decode_problem(B, Hq, Hkv, D, dtype, kv_layout, kv_seq_stride, scale);
+    void* ws = nullptr;
+    int rc = static_scratch(&ws);
+    if (rc != LEAN_ATTN_OK) return rc;
+    // every check first, so that on error nothing is launched, not even the clearing below
+    rc = attend_on(&p, q, k_cache, v_cache, seqlens, out, lse, ws, kStaticScratchBytes, tuning, hip_stream, true,
+                   LEAN_ATTN_STATIC_MAX_GRID);
+    if (rc == LEAN_ATTN_ERR_WORKSPACE) return LEAN_ATTN_ERR_STATIC_LIMIT;
+    if (rc != LEAN_ATTN_OK) return rc;
+    // The array keeps what the last call left.  A call that ran to its end left every flag cleared,
+    // one that gave up waiting may not have: the status word and the flags start at zero every time
+    // (a fill kernel, not a memset: the call may be under graph capture).
+    const int n = (int)(kPartialsOffset / 4);
+    hipLaunchKernelGGL(lean_workspace_clear_kernel, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)hip_stream,
+                       (uint32_t*)ws, n);
+    if (hipGetLastError() != hipSuccess) return LEAN_ATTN_ERR_HIP;
+    return attend_on(&p, q, k_cache, v_cache, seqlens, out, lse, ws, kStaticScratchBytes, tuning, hip_stream, false,
+                     LEAN_ATTN_STATIC_MAX_GRID);
+}
+
 int lean_attn_read_probe(const void* buf, size_t bytes, void* sink, int grid, int mode, void* hip_stream) {
     if (!buf || !sink) return LEAN_ATTN_ERR_NULL_POINTER;
     if (bytes == 0 || (bytes & 15) != 0 || ((uintptr_t)buf & 15) != 0 || grid <= 0 || grid > 65535 || mode < 0 ||
@@ -737,6 +789,7 @@ const char* lean_attn_strerror(int status) {
         case LEAN_ATTN_ERR_HIP: return "a HIP runtime call failed";
         case LEAN_ATTN_ERR_TUNING: return "tuning field out of range";
         case LEAN_ATTN_ERR_PEER_TIMEOUT: return "a host workgroup gave up waiting for a peer's partial";
+        case LEAN_ATTN_ERR_STATIC_LIMIT: return "the launch needs more partial slots than the static scratch of lean_attn_decode_static holds (LEAN_ATTN_STATIC_MAX_GRID workgroups)";
         default: return "unknown status";
     }
 }

@@ -23,6 +23,12 @@ inline __host__ __device__ int slot_floats(int T_m, int D) {
     return (n + 63) & ~63;  // 256-byte slots
 }
 
+// The largest slot any supported tile needs: 32 rows at D = 128 or 16 rows at D = 256.
+constexpr int slot_floats_max() {
+    constexpr int a = (32 * (128 + 2) + 63) & ~63, b = (16 * (256 + 2) + 63) & ~63, c = (32 * (64 + 2) + 63) & ~63;
+    return a > b ? (a > c ? a : c) : (b > c ? b : c);
+}
+
 struct DecodeArgs {
     const uint16_t* q;
     const uint16_t* k;
