@@ -107,6 +107,8 @@ typedef struct lean_attn_plan {
     int32_t fixed_split;      /* 0: stream-K spans; s >= 1: baseline schedule, s parts per output tile,
                                  CTA g = tile_idx*s + part, grid = num_output_tiles*s */
     int32_t C_m;              /* row blocks per KV head */
+    int32_t tile_shape;       /* the compiled tile shape used, 1..6 (lean_attn_tuning.tile_shape, or the library's
+                                 default for this head dim, dtype and T_m) */
 } lean_attn_plan;
 
 /*
@@ -119,21 +121,31 @@ typedef struct lean_attn_tuning {
     int32_t ctas_per_cu;   /* workgroups per compute unit used to size the default G */
     int32_t num_cus;       /* pretend the device has this many compute units (schedule queries) */
     int32_t kernel;        /* 0 default, 1 force VALU kernel (needs N_q * Hq == Hkv), 2 force MFMA kernel */
-    int32_t xcd_remap;     /* 0 default, 1 off, 2 on: place consecutive spans on one XCD */
+    int32_t reserved_;     /* must be 0 */
     int32_t spin_limit;    /* polls before a waiting CTA gives up and reports PEER_TIMEOUT */
     int32_t merge_fanin;   /* partials a CTA merges per level of the reduction tree; 0 default (8; 32 for
                               single-row tiles, which merge a level as wide as the workgroup),
                               >= LEAN_ATTN_MAX_GRID gives Algorithm 2's flat list: the host block
                               merges every peer itself */
-    int32_t tile_shape;    /* 0 default; 1..5 other compiled (loads per lane, waves per workgroup)
-                              shapes, i.e. other LeanTile sizes T_n: see lean_attn_schedule */
+    int32_t tile_shape;    /* 0: the library's default for the head dim, dtype and rows per tile (a table filled
+                              from the LeanTile sweep); 1..6: a compiled (loads or token blocks per wave, waves
+                              per workgroup, buffering) shape, i.e. another LeanTile size T_n: lean_attn_schedule
+                              reports T_n and the shape used */
     int32_t grid_multiple; /* default G = units x ctas_per_cu x grid_multiple (0: library default) */
     int32_t fixed_split;   /* 0: LeanAttention's stream-K spans.  Baseline schedules of Sections 3.3 / 4.3:
                               s >= 1 cuts every output tile into s near-equal parts (s = 1: no split,
                               the FlashAttention-2 schedule), -1 picks s = units*ctas_per_cu / tiles */
-    void* cta_clock;       /* device, 8 uint64 per CTA of the grid, or NULL: 100 MHz timestamps at
-                              kernel entry, end of streaming, end of merging, exit (last segment),
-                              then the HW_ID and XCC_ID registers and the workgroup id, one spare */
+    int32_t debug_delay_store;  /* tests: publishing workgroups sleep this many periods (about 3.4 us each, at
+                                   most 64) before they store their partial ... */
+    int32_t debug_delay_signal; /* ... and this many between the acknowledged stores and the flag store
+                                   (widens the window between StorePartials and Signal of Algorithm 2) */
+    int32_t debug_delay_stride; /* only workgroups with id % stride == stride - 1 sleep (0 or 1: all of them) */
+    int32_t reserved2_;         /* must be 0 */
+    void* cta_clock;       /* device, 16 uint64 per CTA of the grid, or NULL: 100 MHz timestamps
+                              [0] kernel entry, [1] end of the span loop, [2] first segment located, [3] exit,
+                              [7] first LeanTile iteration done, [8] first segment streamed, [9] partial stores
+                              issued, [10] stores acknowledged, [11] peers' flags seen, [12] peers merged,
+                              [13] output written; [4] HW_ID, [5] XCC_ID registers, [6] the workgroup id */
 } lean_attn_tuning;
 
 /*
@@ -202,9 +214,10 @@ int lean_attn_workspace_init(void* workspace, size_t workspace_bytes, void* hip_
 
 /*
  * Blocking: waits for `hip_stream`, then reports LEAN_ATTN_ERR_PEER_TIMEOUT if
- * a host CTA of an earlier call on this workspace gave up waiting for a peer
- * (its output rows are then invalid), else LEAN_ATTN_OK.  Clears the report and,
- * after a timeout, all flags, so the workspace can be used again.
+ * a merging CTA of an earlier call on this workspace gave up waiting for a peer
+ * (after tuning->spin_limit polls or half a second; its output rows are then
+ * invalid), else LEAN_ATTN_OK.  Clears the report and, after a timeout, all
+ * flags, so the workspace can be used again.
  */
 int lean_attn_workspace_status(void* workspace, void* hip_stream);
 

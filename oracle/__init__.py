@@ -10,8 +10,9 @@ Contents
 ``rescale.py``         partial statistics and the softmax re-scaling operator
                        f(x, y) of Section 4.1, in fp64 numpy (test support: lets
                        the definition be checked by split-and-merge).
-``lean_alg2.py``       Algorithms 1 and 2 taken step by step in fp64 numpy over
-                       sequentially emulated CTAs (pins the span bookkeeping).
+``stream_k.py``        the stream-K decomposition of Section 4.3 as interval arithmetic
+                       (span edges x tile edges), its pieces folded with f in any
+                       order (pins the span bookkeeping of the kernel's walk).
 
 Every function here is pinned by ``tests/test_oracle_pins.py`` against closed
 forms, hand-computed cases, invariants and brute-force split/merge; none is

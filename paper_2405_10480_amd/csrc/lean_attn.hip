@@ -8,125 +8,69 @@
 #include <mutex>
 
 #include "../../include/lean_attn.h"
+#include "lean_aux_kernels.h"
 #include "lean_device.h"
-#include "lean_gqa_core.h"
-#include "lean_kernel.h"
-#include "lean_mha_core.h"
 #include "lean_sched.h"
+#include "lean_variants.h"
 
 namespace lean {
 
 static_assert(kMaxBatch == LEAN_ATTN_MAX_BATCH, "header and scheduler disagree on the batch limit");
 static_assert(kMaxGrid == LEAN_ATTN_MAX_GRID, "header and workspace layout disagree on the grid limit");
 
-// Kernel variants: core x dtype x head dim x tile shape.
-//   VALU core:  U loads of 16 bytes per lane for K and again for V per step, NW waves;
-//               LeanTile T_n = NW * U * 64/(D/8) tokens.
-//   MFMA core:  NBLK blocks of 16 tokens per wave per step, NW waves; T_n = NW * NBLK * 16.
-// Shape 0 is the default, picked by the LeanTile sweep on MI355X (the paper fixes the tile
-// size per architecture after an empirical sweep, Section 4.2): with non-temporal loads the
-// memory system runs fastest with about 8 KiB in flight per wave and one workgroup per
-// compute unit of four waves, single-buffered: T_n = 64 tokens at D = 128 for both cores.  The
-// MFMA core's bytes in flight scale with the row length, so its default is eight waves at
-// D = 64 and two token blocks per wave at D = 256 (see gqa_shape).
+// Defaults picked by the LeanTile sweep on MI355X (the paper fixes the tile size per architecture
+// after an empirical sweep, Section 4.2).
 constexpr int kDefaultCtasPerCu = 1;
 constexpr int kShortContextTokens = 1536;  // mean context at or below which two workgroups share a unit
 constexpr int kDefaultFanin = 8;
 constexpr int kDefaultFaninSingleRow = 32;
 constexpr int kDefaultGridMultiple = 1;
 constexpr int kMaxProbeMode = 6;
-constexpr int kNumShapes = 6;
-
-struct Variant {
-    const void* fn;           // arguments by value
-    const void* fn_indirect;  // arguments read from a device block (built for the default shapes only)
-    int T_n;
-    int threads;
-};
-
-template <class Core, bool INDIRECT = false>
-static Variant variant_of() {
-    const void* indirect = nullptr;
-    if constexpr (INDIRECT) indirect = reinterpret_cast<const void*>(&lean_decode_kernel_indirect<Core>);
-    return Variant{reinterpret_cast<const void*>(&lean_decode_kernel<Core>), indirect, Core::kTn, Core::kThreads};
-}
-
-template <int DT, int D>
-static Variant mha_shape(int shape) {  // <loads per lane per stream, waves, double-buffered>
-    switch (shape) {
-        case 0: return variant_of<MhaCore<DT, D, 4, 4, false>, true>();
-        case 1: return variant_of<MhaCore<DT, D, 8, 4, true>>();
-        case 2: return variant_of<MhaCore<DT, D, 4, 4, true>>();
-        case 3: return variant_of<MhaCore<DT, D, 8, 4, false>>();
-        case 4: return variant_of<MhaCore<DT, D, 8, 8, false>>();
-        default: return variant_of<MhaCore<DT, D, 4, 8, false>>();
-    }
-}
-
-template <int DT, int D>
-static Variant gqa_shape(int shape) {  // <16-token blocks per wave per step, waves, double-buffered>
-    // The default keeps 32 KiB or more in flight per compute unit with rows of any length:
-    // eight waves at D = 64 (4 KiB per wave and step), two blocks per wave at D = 256.
-    if (shape == 0 && D == 64) shape = 4;
-    if (shape == 0 && D == 256) shape = 5;
-    switch (shape) {
-        case 0: return variant_of<GqaCore<DT, D, 1, 4, false>, D == 128>();
-        case 1: return variant_of<GqaCore<DT, D, 2, 4, true>>();
-        case 2: return variant_of<GqaCore<DT, D, 1, 4, true>>();
-        case 3: return variant_of<GqaCore<DT, D, 1, 8, true>>();
-        case 4: return variant_of<GqaCore<DT, D, 1, 8, false>, D == 64>();
-        default: return variant_of<GqaCore<DT, D, 2, 4, false>, D == 256>();
-    }
-}
-
-// Two blocks of 16 query rows per pass over K/V (17..32 rows per output tile, D <= 128).
-template <int DT, int D>
-static Variant gqa_shape_two_blocks(int shape) {
-    if (shape == 0) shape = D == 64 ? 1 : 5;  // measured best: two token blocks per wave, double-buffered at D = 64
-    switch (shape) {
-        case 0: return variant_of<GqaCore<DT, D, 1, 4, false, 2>>();
-        case 1: return variant_of<GqaCore<DT, D, 2, 4, true, 2>, D == 64>();
-        case 2: return variant_of<GqaCore<DT, D, 1, 4, true, 2>>();
-        case 3: case 4: return variant_of<GqaCore<DT, D, 1, 8, false, 2>>();
-        default: return variant_of<GqaCore<DT, D, 2, 4, false, 2>, D == 128>();
-    }
-}
 
 static int dim_index(int D) { return D == 64 ? 0 : D == 128 ? 1 : D == 256 ? 2 : -1; }
 
 // Most query rows one output tile can hold: two MFMA row blocks up to D = 128, one at D = 256.
 static int max_tile_rows(int D) { return D <= 128 ? LEAN_ATTN_MAX_TILE_ROWS : 16; }
 
+// Rows-per-tile classes the defaults are keyed on: 1 | 2..8 | 9..16 | 17..32.
+static int row_class(int T_m) { return T_m <= 1 ? 0 : T_m <= 8 ? 1 : T_m <= 16 ? 2 : 3; }
+
+// Default tile shape (1..kNumShapes, see lean_kernels.hip for what each number builds) per
+// [dtype f16, bf16][head dim 64, 128, 256][row class].  With non-temporal loads the memory system
+// runs fastest with about 8 KiB in flight per wave and one four-wave workgroup per compute unit,
+// single-buffered: shape 6 (T_n = 64 tokens at D = 128) for single rows and for one row block at
+// D = 128.  The MFMA core's bytes in flight scale with the row length, so it takes eight waves at
+// D = 64 (shape 4) and two token blocks per wave at D = 256 (shape 5); two row blocks take two
+// token blocks per wave (shape 5; double-buffered, shape 1, at D = 64).
+static const int8_t kDefaultShape[2][3][4] = {
+    /* f16  */ {{6, 4, 4, 1}, {6, 6, 6, 5}, {6, 5, 5, 0}},
+    /* bf16 */ {{6, 4, 4, 1}, {6, 6, 6, 5}, {6, 5, 5, 0}},
+};
+
+// kernel: 0 VALU single-row core, 1 MFMA query-group core; T_m: query rows per output tile;
+// shape: 0 = the default of the table, 1..kNumShapes a compiled shape.  *resolved gets the shape used.
+static bool pick_variant(int kernel, int dtype, int D, int shape, int T_m, Variant* v, int* resolved = nullptr) {
+    if (shape < 0 || shape > kNumShapes || dim_index(D) < 0 || T_m < 1 || T_m > max_tile_rows(D)) return false;
+    if (dtype != LEAN_ATTN_F16 && dtype != LEAN_ATTN_BF16) return false;
+    const bool bf = dtype == LEAN_ATTN_BF16;
+    // the MFMA core on a single row is served by the one-block defaults
+    if (shape == 0) shape = kDefaultShape[bf][dim_index(D)][kernel == 0 ? 0 : (T_m <= 1 ? 1 : row_class(T_m))];
+    if (kernel == 0) *v = bf ? variant_mha_bf16(D, shape) : variant_mha_f16(D, shape);
+    else if (T_m > 16) *v = bf ? variant_gqa2_bf16(D, shape) : variant_gqa2_f16(D, shape);
+    else *v = bf ? variant_gqa_bf16(D, shape) : variant_gqa_f16(D, shape);
+    if (resolved) *resolved = shape;
+    return v->fn != nullptr;
+}
+
 // Workspace bytes a launch of `grid` workgroups with T_m-row partials touches.
 static size_t workspace_need(int64_t grid, int T_m, int D) {
     return kPartialsOffset + (size_t)grid * slot_floats(T_m, D) * sizeof(float);
 }
 
-// kernel: 0 VALU single-row core, 1 MFMA query-group core; T_m: query rows per output tile
-static bool pick_variant(int kernel, int dtype, int D, int shape, int T_m, Variant* v) {
-    if (shape < 0 || shape >= kNumShapes || dim_index(D) < 0 || T_m < 1 || T_m > max_tile_rows(D)) return false;
-    const bool bf = dtype == LEAN_ATTN_BF16;
-    if (kernel == 1 && T_m > 16) {
-        if (D == 64) *v = bf ? gqa_shape_two_blocks<kDtBF16, 64>(shape) : gqa_shape_two_blocks<kDtF16, 64>(shape);
-        else *v = bf ? gqa_shape_two_blocks<kDtBF16, 128>(shape) : gqa_shape_two_blocks<kDtF16, 128>(shape);
-        return true;
-    }
-    if (kernel == 0) {
-        if (D == 64) *v = bf ? mha_shape<kDtBF16, 64>(shape) : mha_shape<kDtF16, 64>(shape);
-        else if (D == 128) *v = bf ? mha_shape<kDtBF16, 128>(shape) : mha_shape<kDtF16, 128>(shape);
-        else *v = bf ? mha_shape<kDtBF16, 256>(shape) : mha_shape<kDtF16, 256>(shape);
-    } else {
-        if (D == 64) *v = bf ? gqa_shape<kDtBF16, 64>(shape) : gqa_shape<kDtF16, 64>(shape);
-        else if (D == 128) *v = bf ? gqa_shape<kDtBF16, 128>(shape) : gqa_shape<kDtF16, 128>(shape);
-        else *v = bf ? gqa_shape<kDtBF16, 256>(shape) : gqa_shape<kDtF16, 256>(shape);
-    }
-    return true;
-}
-
 // Unit count of the device and, per variant, the workgroups that fit on one unit (cached).
 struct DeviceInfo {
     int cus = 0;
-    int resident[3][2][3][kNumShapes] = {};  // [VALU, MFMA, MFMA two row blocks][dtype][head dim][shape], 0 = not yet queried
+    int resident[3][2][3][kNumShapes + 1] = {};  // [VALU, MFMA, MFMA two row blocks][dtype][head dim][shape], 0 = not yet queried
 };
 static DeviceInfo g_dev[64];
 static std::mutex g_dev_mutex;
@@ -142,10 +86,11 @@ static int query_device(int kernel, int dtype, int D, int shape, int T_m, int* c
         di.cus = prop.multiProcessorCount;
     }
     if (dim_index(D) < 0) return LEAN_ATTN_ERR_UNSUPPORTED;
-    int& n = di.resident[kernel == 1 && T_m > 16 ? 2 : kernel][dtype][dim_index(D)][shape];
+    Variant v;
+    int resolved = 0;
+    if (!pick_variant(kernel, dtype, D, shape, T_m, &v, &resolved)) return LEAN_ATTN_ERR_UNSUPPORTED;
+    int& n = di.resident[kernel == 1 && T_m > 16 ? 2 : kernel][dtype][dim_index(D)][resolved];
     if (n == 0) {
-        Variant v;
-        if (!pick_variant(kernel, dtype, D, shape, T_m, &v)) return LEAN_ATTN_ERR_UNSUPPORTED;
         int blocks = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, v.fn, v.threads, 0) != hipSuccess || blocks <= 0)
             return LEAN_ATTN_ERR_HIP;
@@ -226,9 +171,10 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
     lean_attn_tuning t;
     std::memset(&t, 0, sizeof t);
     if (tn) t = *tn;
-    if (t.grid < 0 || t.ctas_per_cu < 0 || t.num_cus < 0 || t.kernel < 0 || t.kernel > 2 || t.xcd_remap < 0 ||
-        t.xcd_remap > 2 || t.spin_limit < 0 || t.merge_fanin < 0 || t.merge_fanin == 1 || t.tile_shape < 0 ||
-        t.tile_shape >= kNumShapes || t.grid_multiple < 0 || t.fixed_split < -1)
+    if (t.grid < 0 || t.ctas_per_cu < 0 || t.num_cus < 0 || t.kernel < 0 || t.kernel > 2 || t.reserved_ != 0 ||
+        t.debug_delay_store < 0 || t.debug_delay_store > 64 ||
+        t.debug_delay_signal < 0 || t.debug_delay_signal > 64 || t.debug_delay_stride < 0 || t.spin_limit < 0 || t.merge_fanin < 0 || t.merge_fanin == 1 || t.tile_shape < 0 ||
+        t.tile_shape > kNumShapes || t.grid_multiple < 0 || t.fixed_split < -1)
         return LEAN_ATTN_ERR_TUNING;
     const int T_m = rb.T_m;
     // the single-row core indexes q and out by (b, head): per-sequence query lengths go to the MFMA core
@@ -240,7 +186,8 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
         kernel = 1;
     }
     Variant var;
-    if (!pick_variant(kernel, dtype, D, t.tile_shape, T_m, &var)) return LEAN_ATTN_ERR_UNSUPPORTED;
+    int tile_shape = 0;
+    if (!pick_variant(kernel, dtype, D, t.tile_shape, T_m, &var, &tile_shape)) return LEAN_ATTN_ERR_UNSUPPORTED;
     const int T_n = var.T_n;
 
     int64_t iters = 0, toks = 0, q_toks = 0;
@@ -327,6 +274,7 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
     plan->kernel = kernel;
     plan->fixed_split = split;
     plan->C_m = rb.C_m;
+    plan->tile_shape = tile_shape;
     if (sched) {
         sched->B = B;
         sched->Hkv = heads;
@@ -337,7 +285,7 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
         sched->total_iters = I;
         sched->iters_per_cta = plan->iters_per_cta;
         sched->fixed_split = split;
-        sched->pad_ = 0;
+        if (table) finish_sched(*sched, *table);
     }
     return LEAN_ATTN_OK;
 }
@@ -436,7 +384,7 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
     s.total_iters = plan->total_iters;
     s.iters_per_cta = plan->iters_per_cta;
     s.fixed_split = plan->fixed_split;
-    s.pad_ = 0;
+    finish_sched(s, t);
     if (iters * heads != plan->total_iters) return LEAN_ATTN_ERR_BAD_SHAPE;
     int64_t it, end;
     span_of(s, t, g, &it, &end);
@@ -521,8 +469,9 @@ static int build_launch(const lean_attn_problem& p, const void* q, const void* k
     a.causal = p.causal;
     a.out16 = p.out_dtype == LEAN_ATTN_OUT_AS_INPUT;
     a.slot = slot_floats(rb.T_m, D);
-    // the remap permutes span ids against dispatch order: only safe while the whole grid is resident
-    a.xcd_remap = (tuning && tuning->xcd_remap == 2 && plan->grid <= plan->max_resident) ? 1 : 0;
+    a.delay_store = tuning ? tuning->debug_delay_store : 0;
+    a.delay_signal = tuning ? tuning->debug_delay_signal : 0;
+    a.delay_stride = tuning ? tuning->debug_delay_stride : 0;
     a.spin_limit = (tuning && tuning->spin_limit > 0) ? tuning->spin_limit : (1 << 22);
     a.has_empty = has_empty;
     // single-row tiles merge a whole level of up to 32 partials in one round trip (see merge_children_wide)

@@ -51,11 +51,13 @@ struct DecodeArgs {
     int32_t causal;        // row of query token i sees the first N_b - N_q + i + 1 cached tokens
     int32_t out16;         // out holds 16-bit elements
     int32_t slot;          // floats per partial slot
-    int32_t xcd_remap;
     int32_t spin_limit;
     int32_t has_empty;     // some N_b == 0: those output rows must be zeroed
     int32_t fanin;         // children merged per level of the reduction tree (>= 2)
-    unsigned long long* cta_clock;  // optional trace, 8 words per CTA, may be null
+    int32_t delay_store;   // debug: a publishing workgroup sleeps this many periods before its partial stores
+    int32_t delay_signal;  // debug: ... and this many between the acknowledged stores and its flag store
+    int32_t delay_stride;  // debug: only workgroups with g % stride == stride - 1 sleep (0 or 1: all)
+    unsigned long long* cta_clock;  // optional trace, kClockWords words per CTA, may be null
     float scale_log2e;     // scale * log2(e): scores live in the base-2 domain
     Sched sched;
     SchedTable table;
@@ -196,9 +198,14 @@ __device__ __forceinline__ float xor_shuffle(float x, int lane_mask) { return __
 // is itself a device-scope access (the sc1 cache-policy bit: written through to, and read
 // from, the device coherence point), so no cache-wide writeback or invalidate is needed:
 //   producer: sc1 stores of the partial; wait until they are acknowledged (s_waitcnt
-//             vmcnt(0), part of the workgroup barrier); then one sc1 store of the flag;
+//             vmcnt(0), then the workgroup barrier); then one sc1 store of the flag;
 //   consumer: sc1 loads of the flag until set; then sc1 loads of the partial.
+// (Narrower scopes were measured and dropped: a polling load with sc0 is served again and again
+// from the compute unit's own cache and never sees the flag; between two workgroups of one XCD
+// an sc0 store is seen by an sc1 poll after 0.3-0.4 us, an sc1 store after 0.4-0.6 us, between
+// XCDs after 0.5-0.8 us: too little to pay for a second protocol.)
 constexpr int kDeviceScope = 16;  // cache-policy operand of the buffer builtins: sc1
+constexpr uint32_t kStatusTimeout = 1u;  // status word: a merging workgroup gave up waiting for a peer
 
 __device__ __forceinline__ void partial_store16(buffer_rsrc r, uint32_t byte_off, f32x4 v) {
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)byte_off, 0, kDeviceScope);
@@ -213,26 +220,37 @@ __device__ __forceinline__ float partial_load4(buffer_rsrc r, uint32_t byte_off)
     return as_f32(__builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, kDeviceScope));
 }
 
-// Signal: the barrier waits for every thread's partial stores to be acknowledged.
-__device__ __forceinline__ void signal_arrival(uint32_t* flag) {
-    __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): stores acknowledged
-    __syncthreads();
-    if (threadIdx.x == 0) __hip_atomic_store(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ void debug_sleep(int periods) {
+    for (int i = 0; i < periods; ++i) __builtin_amdgcn_s_sleep(127);  // about 3.4 us each
+}
+__device__ __forceinline__ bool debug_delayed(const DecodeArgs& a, int g) {
+    return a.delay_stride <= 1 || g % a.delay_stride == a.delay_stride - 1;
 }
 
-// Wait for `nchild` peers at once: thread j polls the flag of CTA first + j*step (bounded).
-// The consumer clears the flags: each flag has exactly one consumer per launch, so the
-// workspace is clean again when the kernel ends.
-__device__ __forceinline__ void wait_arrivals(uint32_t* flags, int first, int step, int nchild, uint32_t* status,
-                                              int spin_limit) {
+// Signal: the barrier waits for every thread's partial stores to be acknowledged.
+__device__ __forceinline__ void signal_arrival(const DecodeArgs& a, int g) {
+    __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): stores acknowledged
+    __syncthreads();
+    if (a.delay_signal && debug_delayed(a, g)) debug_sleep(a.delay_signal);
+    if (threadIdx.x == 0) __hip_atomic_store(a.flags + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Wait for `nchild` peers at once: thread j polls the flag of CTA first + j*step.  The wait is
+// bounded twice over, by a poll count and by half a second of wall clock (no output tile takes
+// that long): a peer that never arrives is reported, not waited for.  The consumer clears the
+// flags: each flag has exactly one consumer per launch, so the workspace is clean again when
+// the kernel ends.
+constexpr unsigned long long kWaitTicks = 50000000ull;  // 0.5 s of the 100 MHz wall clock
+__device__ __forceinline__ void wait_arrivals(const DecodeArgs& a, int first, int step, int nchild) {
     if ((int)threadIdx.x < nchild) {
-        uint32_t* flag = flags + first + (int)threadIdx.x * step;
+        uint32_t* flag = a.flags + (first + (int)threadIdx.x * step);
+        const unsigned long long t0 = wall_clock64();
         int spins = 0;
         while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-            __builtin_amdgcn_s_sleep(2);
-            if (++spins >= spin_limit) {  // peer never arrived: report, do not hang
-                __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins >= a.spin_limit || ((spins & 255) == 0 && wall_clock64() - t0 > kWaitTicks)) {
+                __hip_atomic_store(a.status, kStatusTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;  // peer never arrived: report, do not hang
             }
         }
         __hip_atomic_store(flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -240,15 +258,21 @@ __device__ __forceinline__ void wait_arrivals(uint32_t* flags, int first, int st
     __syncthreads();  // the partial loads that follow are issued after the flags were seen
 }
 
-// Optional per-CTA trace: 8 uint64 per CTA: timestamps (100 MHz) at kernel entry, end of
-// streaming, end of merging and exit, then the HW_ID and XCC_ID registers and the workgroup id.
+// Optional per-CTA trace: kClockWords uint64 per CTA: 100 MHz timestamps, the HW_ID and XCC_ID
+// registers and the workgroup id.
+constexpr int kClockWords = 16;
+enum ClockSlot {
+    kClkEntry = 0, kClkLoopEnd = 1, kClkLocated = 2, kClkExit = 3, kClkHwId = 4, kClkXccId = 5, kClkBlock = 6,
+    kClkFirstStep = 7, kClkCoreDone = 8, kClkStoresIssued = 9, kClkStoresAcked = 10, kClkFlagsSeen = 11,
+    kClkMerged = 12, kClkWritten = 13
+};
 __device__ __forceinline__ void stamp(const DecodeArgs& a, int g, int slot) {
     if (a.cta_clock && threadIdx.x == 0) {
-        a.cta_clock[8 * g + slot] = wall_clock64();
-        if (slot == 0) {
-            a.cta_clock[8 * g + 4] = __builtin_amdgcn_s_getreg((31 << 11) | 4);   // HW_REG_HW_ID
-            a.cta_clock[8 * g + 5] = __builtin_amdgcn_s_getreg((31 << 11) | 20);  // HW_REG_XCC_ID
-            a.cta_clock[8 * g + 6] = blockIdx.x;
+        a.cta_clock[kClockWords * g + slot] = wall_clock64();
+        if (slot == kClkEntry) {
+            a.cta_clock[kClockWords * g + kClkHwId] = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_REG_HW_ID
+            a.cta_clock[kClockWords * g + kClkXccId] = __builtin_amdgcn_s_getreg((31 << 11) | 20);  // HW_REG_XCC_ID
+            a.cta_clock[kClockWords * g + kClkBlock] = blockIdx.x;
         }
     }
 }

@@ -326,7 +326,7 @@ struct GqaCore {
                 load_tile(v_slab, vB, off_at(k + 1));
                 stage_k(kA);
                 attend(vA, it_first + k);
-                if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+                if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[kClockWords * cta + kClkFirstStep] = wall_clock64();
                 load_tile(k_slab, kA, off_at(k + 2));
                 load_tile(v_slab, vA, off_at(k + 2));
                 if (k + 1 < n_it) {
@@ -344,7 +344,7 @@ struct GqaCore {
                     load_tile(v_slab, vA, off_at(k));
                     stage_k(kA);
                     attend(vA, it_first + k);
-                    if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+                    if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[kClockWords * cta + kClkFirstStep] = wall_clock64();
                 }
             } else {
                 // One register buffer, software-pipelined: the K registers are free as soon as the
@@ -358,7 +358,7 @@ struct GqaCore {
                     load_tile(k_slab, kA, off_at(k + 1));
                     attend(vA, it_first + k);
                     load_tile(v_slab, vA, off_at(k + 1));
-                    if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+                    if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[kClockWords * cta + kClkFirstStep] = wall_clock64();
                 }
             }
         }

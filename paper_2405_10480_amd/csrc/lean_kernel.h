@@ -166,7 +166,8 @@ __device__ __forceinline__ void reduce_tile(const DecodeArgs& a, OwnPartial<CPT>
             constexpr int kWide = 4 * (THREADS / (D / 4));
             while (remaining > 0) {
                 const int batch = remaining < kWide ? remaining : kWide;
-                wait_arrivals(a.flags, child, -(int)stride, batch, a.status, a.spin_limit);
+                wait_arrivals(a, child, -(int)stride, batch);
+                stamp(a, g, kClkFlagsSeen);
                 merge_children_wide<THREADS, D>(a, own, child, -(int)stride, batch, wide_scratch);
                 child -= batch * (int)stride;
                 remaining -= batch;
@@ -174,15 +175,18 @@ __device__ __forceinline__ void reduce_tile(const DecodeArgs& a, OwnPartial<CPT>
         } else {
             while (remaining > 0) {  // batches of at most F-1 partials
                 const int batch = remaining < F - 1 ? remaining : F - 1;
-                wait_arrivals(a.flags, child, -(int)stride, batch, a.status, a.spin_limit);
+                wait_arrivals(a, child, -(int)stride, batch);
+                stamp(a, g, kClkFlagsSeen);
                 merge_children<CPT, THREADS, D, F>(a, own, child, -(int)stride, batch, n_chunks, n_elem, T_m);
                 child -= batch * (int)stride;
                 remaining -= batch;
             }
         }
+        stamp(a, g, kClkMerged);
     }
     if (publish) {
         // StorePartials(Op[g], mp[g], lp[g]); Signal(flags[g])
+        if (a.delay_store && debug_delayed(a, g)) debug_sleep(a.delay_store);
         const buffer_rsrc ws = make_slab((const uint16_t*)a.partials, (uint32_t)a.sched.grid * (uint32_t)a.slot * 4u);
         const uint32_t slot = (uint32_t)g * (uint32_t)a.slot * 4u;
 #pragma unroll
@@ -196,7 +200,9 @@ __device__ __forceinline__ void reduce_tile(const DecodeArgs& a, OwnPartial<CPT>
                 }
             }
         }
-        signal_arrival(a.flags + g);
+        stamp(a, g, kClkStoresIssued);
+        signal_arrival(a, g);
+        stamp(a, g, kClkStoresAcked);
     } else {
         // m is kept in the base-2 domain: L = ln2 * (m + log2 l)
         const TileRows tr = tile_rows(a, b, h);
@@ -218,6 +224,7 @@ __device__ __forceinline__ void reduce_tile(const DecodeArgs& a, OwnPartial<CPT>
                     a.lse[orow] = 0.6931471805599453f * (own.m[i] + __builtin_amdgcn_logf(own.l[i]));
             }
         }
+        stamp(a, g, kClkWritten);
     }
 }
 
@@ -243,22 +250,24 @@ __device__ __forceinline__ void lean_decode_body(const DecodeArgs& a) {
     // keeps the scalar registers free; the first entries of the prefix tables are touched too,
     // so that the table look-ups of small batches hit as well.
     static_assert(offsetof(DecodeArgs, q) < 64 && offsetof(DecodeArgs, kv_seq_stride) / 64 == 1 &&
-                      offsetof(DecodeArgs, spin_limit) / 64 == 2 && offsetof(DecodeArgs, sched.iters_per_cta) / 64 == 3,
+                      offsetof(DecodeArgs, has_empty) / 64 == 2 && offsetof(DecodeArgs, sched.grid) / 64 == 2 &&
+                      offsetof(DecodeArgs, sched.iters_per_cta) / 64 == 3 && offsetof(DecodeArgs, sched.by_cn) / 64 == 3 &&
+                      offsetof(DecodeArgs, table.cu_iters[1]) / 64 == 4,
                   "one touched field per line of the argument block");
-    asm volatile("" ::"s"(a.q), "s"(a.kv_seq_stride), "s"(a.spin_limit), "s"(a.sched.iters_per_cta),
+    asm volatile("" ::"s"(a.q), "s"(a.kv_seq_stride), "s"(a.has_empty), "s"(a.sched.iters_per_cta),
                  "s"(a.table.cu_iters[1]), "s"(a.table.cu_tok[1]));
 
-    // CTA id.  The hardware deals consecutive workgroup ids round-robin to the
-    // 8 XCDs; the optional remap makes the spans of one XCD contiguous so that
-    // the partials a block merges mostly come from its own L2.
-    int g = blockIdx.x;
+    // CTA id = workgroup id: the hardware dispatches workgroups in id order, and a workgroup only
+    // ever waits for lower ids (reduce_tile), so every wait ends however few workgroups are
+    // resident at once.  (Mapping span ids so that consecutive spans share an XCD was tried: no
+    // gain in streaming rate, and a workgroup may then wait for one dispatched after it.)
+    const int g = blockIdx.x;
     const int G = a.sched.grid;
-    if (a.xcd_remap && (G & 7) == 0) g = (g & 7) * (G >> 3) + (g >> 3);
 
     const int tid = threadIdx.x;
     const int T_m = a.T_m;
     const int n_chunks = T_m * D / 4;
-    stamp(a, g, 0);
+    stamp(a, g, kClkEntry);
 
     if (a.has_empty) {  // sequences with N_b = 0 own no iteration: their rows are defined as zero
         const int row_words = a.out16 ? D / 2 : D;  // zero bits are 0.0 in every output type
@@ -284,7 +293,7 @@ __device__ __forceinline__ void lean_decode_body(const DecodeArgs& a) {
     Segment sg;
     while (it < cta_end) {
         sg = it == cta_start ? locate(a.sched, a.table, it, cta_end) : locate_next(a.sched, a.table, sg, g, cta_end);
-        if (it == cta_start) stamp(a, g, 2);
+        if (it == cta_start) stamp(a, g, kClkLocated);
         if (a.ragged_q && tile_rows(a, sg.b, sg.h).count <= 0) {
             // a sequence with fewer query tokens than the longest: this row block holds no rows.
             // Every CTA of the tile sees the same count, so none computes, publishes or waits.
@@ -292,6 +301,7 @@ __device__ __forceinline__ void lean_decode_body(const DecodeArgs& a) {
             continue;
         }
         Core::run(a, sg, sm, g);  // ends with a workgroup barrier
+        if (it == cta_start) stamp(a, g, kClkCoreDone);
 
         // Fold the per-wave partial streams into the workgroup's partial.
         OwnPartial<CPT> own;
@@ -336,7 +346,7 @@ __device__ __forceinline__ void lean_decode_body(const DecodeArgs& a) {
         it = sg.tile_iter_end;
         __syncthreads();  // the cores reuse the shared partial streams
     }
-    stamp(a, g, 1);
+    stamp(a, g, kClkLoopEnd);
     if (parked) {
         OwnPartial<CPT> own;
 #pragma unroll
@@ -347,7 +357,7 @@ __device__ __forceinline__ void lean_decode_body(const DecodeArgs& a) {
         }
         reduce_tile<Core, CPT, F>(a, own, g, parked_b, parked_h, parked_first, g, wide_scratch);
     }
-    stamp(a, g, 3);
+    stamp(a, g, kClkExit);
 }
 
 // The arguments travel by value in the kernel argument segment ...
@@ -362,121 +372,6 @@ template <class Core>
 __global__ __launch_bounds__(Core::kThreads, Core::kMinWavesPerSimd) void lean_decode_kernel_indirect(
     const DecodeArgs* __restrict__ block) {
     lean_decode_body<Core>(*block);
-}
-
-// Clears flags and status of a fresh workspace (a fill kernel: safe under graph capture).
-__global__ void lean_workspace_clear_kernel(uint32_t* words, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) words[i] = 0u;
-}
-
-// All sequences empty: only zeros to write.
-__global__ void lean_zero_rows_kernel(uint32_t* out_words, float* lse, int64_t rows, int row_words) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < rows * row_words) out_words[i] = 0u;
-    if (lse && i < rows) lse[i] = -INFINITY;
-}
-
-// Streaming-read probe: 16-byte loads, 8 in flight per lane, folded into one word so the
-// loads cannot be dropped.  mode 0: workgroup g reads the g-th contiguous share of the
-// buffer (the access pattern of contiguous stream-K spans); mode 1: the workgroups sweep
-// the buffer together, 32 KiB chunks dealt round-robin (grid-stride); modes 2..4: as mode 0
-// through a buffer descriptor with cache policy nt, sc1, sc0|sc1 on the loads.
-template <int AUX>
-__device__ __forceinline__ uint32_t probe_slab(const uint4* buf, int64_t lo, int64_t hi) {
-    uint32_t acc = 0;
-    const int64_t span = hi - lo;  // 16-byte units, < 2^27 per workgroup
-    const buffer_rsrc r = make_slab((const uint16_t*)(buf + lo), (uint32_t)(span * 16));
-    for (int64_t i = threadIdx.x; i + 7 * 256 < span; i += 8 * 256) {
-        u32x4 x[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = __builtin_amdgcn_raw_buffer_load_b128(r, (int)((i + u * 256) * 16), 0, AUX);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
-    }
-    return acc;
-}
-
-// mode 5: the K access pattern of the MFMA core: per wave-wide load, lane (r = lane%16,
-// g = lane/16) reads 16 bytes of row r at byte 64*c + 16*g of a 256-byte row (non-temporal).
-__device__ __forceinline__ uint32_t probe_rowstrided(const uint4* buf, int64_t lo, int64_t hi) {
-    uint32_t acc = 0;
-    const int64_t span = hi - lo;
-    const buffer_rsrc r = make_slab((const uint16_t*)(buf + lo), (uint32_t)(span * 16));
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const uint32_t lane_off = (uint32_t)(lane & 15) * 256u + (uint32_t)(lane >> 4) * 16u;
-    // a workgroup step = 4 waves x 2 blocks of 16 rows x 256 B = 32 KiB
-    for (int64_t i = 0; (i + 1) * 2048 <= span; ++i) {
-        const uint32_t base = (uint32_t)(i * 32768) + (uint32_t)w * 8192u + lane_off;
-        u32x4 x[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-            x[u] = __builtin_amdgcn_raw_buffer_load_b128(r, (int)(base + (u >> 2) * 4096u + (u & 3) * 64u), 0, 2);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
-    }
-    return acc;
-}
-
-// mode 6: the K/V access pattern of the MFMA core at D = 256: per wave-wide load, lane (r, g)
-// reads 16 bytes at byte 16*r of one half (256 bytes) of row g of a 4-row group; the two halves
-// of the rows come from consecutive load instructions (non-temporal).
-__device__ __forceinline__ uint32_t probe_halfrows(const uint4* buf, int64_t lo, int64_t hi) {
-    uint32_t acc = 0;
-    const int64_t span = hi - lo;
-    const buffer_rsrc r = make_slab((const uint16_t*)(buf + lo), (uint32_t)(span * 16));
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const uint32_t lane_off = (uint32_t)(lane >> 4) * 512u + (uint32_t)(lane & 15) * 16u;
-    // a workgroup step = 4 waves x 16 rows x 512 B = 32 KiB
-    for (int64_t i = 0; (i + 1) * 2048 <= span; ++i) {
-        const uint32_t base = (uint32_t)(i * 32768) + (uint32_t)w * 8192u + lane_off;
-        u32x4 x[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-            x[u] = __builtin_amdgcn_raw_buffer_load_b128(r, (int)(base + (u >> 1) * 2048u + (u & 1) * 256u), 0, 2);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
-    }
-    return acc;
-}
-
-__global__ __launch_bounds__(256) void lean_read_probe_kernel(const uint4* buf, int64_t n_vec, uint32_t* sink,
-                                                              int mode) {
-    const int G = gridDim.x;
-    uint32_t acc = 0;
-    int64_t lo, hi, step;
-    if (mode != 1) {
-        const int64_t per = (n_vec + G - 1) / G;
-        lo = (int64_t)blockIdx.x * per;
-        hi = lo + per < n_vec ? lo + per : n_vec;
-        step = 8 * 256;
-    } else {
-        lo = (int64_t)blockIdx.x * (8 * 256);
-        hi = n_vec;
-        step = (int64_t)G * (8 * 256);
-    }
-    if (mode >= 2) {
-        if (lo < hi)
-            acc = mode == 2 ? probe_slab<2>(buf, lo, hi) : mode == 3 ? probe_slab<16>(buf, lo, hi)
-                  : mode == 4 ? probe_slab<17>(buf, lo, hi)
-                  : mode == 5 ? probe_rowstrided(buf, lo, hi) : probe_halfrows(buf, lo, hi);
-    } else {
-        int64_t i = lo + threadIdx.x;
-        for (; i + 7 * 256 < hi; i += step) {
-            uint4 x[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) x[u] = buf[i + u * 256];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) acc ^= x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
-        }
-        if (mode == 0 || i < hi) {  // ragged end: at most one partial chunk per workgroup
-            for (; i < hi; i += 256) {
-                const uint4 x = buf[i];
-                acc ^= x.x ^ x.y ^ x.z ^ x.w;
-            }
-        }
-    }
-    if (acc == 0x9e3779b9u) sink[0] = acc;  // practically never true: keeps the loads alive
 }
 
 }  // namespace lean

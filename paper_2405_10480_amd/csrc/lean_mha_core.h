@@ -151,7 +151,7 @@ struct MhaCore {
                 load_tile(v_slab, vB, off_at(k + 1));
                 scores(kA, s);
                 attend(s, vA, it_first + k);
-                if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+                if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[kClockWords * cta + kClkFirstStep] = wall_clock64();
                 load_tile(k_slab, kA, off_at(k + 2));
                 load_tile(v_slab, vA, off_at(k + 2));
                 if (k + 1 < n_it) {
@@ -170,7 +170,7 @@ struct MhaCore {
                 load_tile(v_slab, vA, off_at(k));
                 scores(kA, s);
                 attend(s, vA, it_first + k);
-                if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[8 * cta + 7] = wall_clock64();
+                if (a.cta_clock && k == 0 && threadIdx.x == 0) a.cta_clock[kClockWords * cta + kClkFirstStep] = wall_clock64();
             }
         }
 

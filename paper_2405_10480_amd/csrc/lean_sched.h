@@ -37,6 +37,34 @@ struct SchedTable {
     int32_t cu_q[kMaxBatch + 1];      // sum_{b'<b} query tokens of b' (read only with per-sequence query lengths)
 };
 
+// Division of a 31-bit dividend by a divisor fixed per launch, as a multiplication: the span walk
+// runs on one wave's scalar unit before the first K/V load can be issued, and a hardware-less
+// 32-bit division costs it some 40 dependent instructions, four times per segment.
+// For 0 <= n < 2^31 and d >= 1:  n / d == (n * mul) >> (32 + shift)  with mul = ceil(2^(31+s) / d),
+// s = ceil(log2 d), shift = s - 1 (Granlund & Montgomery: an N-bit multiplier suffices for
+// dividends of N-1 bits); d = 1 is encoded as mul = 0.
+struct Magic {
+    uint32_t mul;
+    uint32_t shift;
+};
+inline Magic make_magic(uint32_t d) {
+    Magic m = {0u, 0u};
+    if (d <= 1) return m;
+    uint32_t s = 0;
+    while ((1ull << s) < d) ++s;
+    m.mul = (uint32_t)(((1ull << (31 + s)) + d - 1) / d);
+    m.shift = s - 1;
+    return m;
+}
+LEAN_HD uint32_t magic_div(uint32_t n, Magic m) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const uint32_t hi = __umulhi(n, m.mul);
+#else
+    const uint32_t hi = (uint32_t)(((uint64_t)n * m.mul) >> 32);
+#endif
+    return m.mul ? hi >> m.shift : n;
+}
+
 struct Sched {
     int32_t B;
     int32_t Hkv;            // output tiles per sequence: KV heads x row blocks per KV head (C_m)
@@ -47,7 +75,13 @@ struct Sched {
     int64_t total_iters;    // I
     int64_t iters_per_cta;  // I / G
     int32_t fixed_split;    // 0: stream-K spans; s >= 1: fixed split into s parts per output tile
-    int32_t pad_;
+    int32_t uniform_cn;     // > 0: every sequence owns this many LeanTile iterations (no table search)
+    // multipliers for the divisors of the walk; valid (and used) only while I < 2^31 - 1
+    Magic by_ipc;           // iters_per_cta
+    Magic by_ipc1;          // iters_per_cta + 1
+    Magic by_heads;         // Hkv (PADDED order: iteration -> sequence key)
+    Magic by_per_head;      // cuC[B] (PACKED order: iteration -> head)
+    Magic by_cn;            // uniform_cn
 };
 
 // One output-tile segment of a CTA's span (one trip of Algorithm 2's loop).
@@ -72,11 +106,34 @@ LEAN_HD int64_t div_iters(const Sched& s, int64_t a, int64_t b) {
     return a / b;
 }
 
+constexpr int64_t kMagicLimit = 0x7fffffff;  // iteration spaces below this divide by multiplication
+
+// Fills the derived fields of a schedule whose B, Hkv, grid, total_iters, iters_per_cta are set.
+inline void finish_sched(Sched& s, const SchedTable& t) {
+    s.uniform_cn = 0;
+    if (s.B >= 1) {
+        const int32_t c0 = t.cu_iters[1] - t.cu_iters[0];
+        bool same = c0 > 0;
+        for (int b = 1; b < s.B && same; ++b) same = t.cu_iters[b + 1] - t.cu_iters[b] == c0;
+        if (same) s.uniform_cn = c0;
+    }
+    const bool small = s.total_iters < kMagicLimit;
+    s.by_ipc = make_magic(small ? (uint32_t)s.iters_per_cta : 1u);
+    s.by_ipc1 = make_magic(small ? (uint32_t)s.iters_per_cta + 1u : 1u);
+    s.by_heads = make_magic(small ? (uint32_t)s.Hkv : 1u);
+    s.by_per_head = make_magic(small && s.B >= 1 ? (uint32_t)t.cu_iters[s.B] : 1u);
+    s.by_cn = make_magic(small && s.uniform_cn > 0 ? (uint32_t)s.uniform_cn : 1u);
+}
+
 // The CTA whose span holds global iteration `it` (stream-K spans).
 LEAN_HD int cta_of_iter(const Sched& s, int64_t it) {
     const int64_t fat = (int64_t)s.extra * (s.iters_per_cta + 1);
-    if (it < fat) return (int)div_iters(s, it, s.iters_per_cta + 1);
-    return s.extra + (int)div_iters(s, it - fat, s.iters_per_cta);
+    if (s.total_iters < kMagicLimit) {
+        if (it < fat) return (int)magic_div((uint32_t)it, s.by_ipc1);
+        return s.extra + (int)magic_div((uint32_t)(it - fat), s.by_ipc);
+    }
+    if (it < fat) return (int)(it / (s.iters_per_cta + 1));
+    return s.extra + (int)((it - fat) / s.iters_per_cta);
 }
 
 // Largest b in [0, B) with cu_iters[b] <= key (key < cu_iters[B]); skips empty sequences.
@@ -94,20 +151,27 @@ LEAN_HD Segment locate(const Sched& s, const SchedTable& t, int64_t it, int64_t 
     Segment sg;
     int64_t tile_iter;  // global index of the tile's first iteration
     int32_t c_n;
+    const bool small = s.total_iters < kMagicLimit;
+    // with equal lengths the sequence of a key is a quotient, otherwise a search in the prefix table
+    auto sequence_of = [&](int32_t key) {
+        if (s.uniform_cn > 0 && small) return (int)magic_div((uint32_t)key, s.by_cn);
+        return find_sequence(t, s.B, key);
+    };
     if (s.packed) {
         const int64_t per_head = t.cu_iters[s.B];
-        sg.h = (int32_t)div_iters(s, it, per_head);
+        sg.h = small ? (int32_t)magic_div((uint32_t)it, s.by_per_head) : (int32_t)(it / per_head);
         const int32_t key = (int32_t)(it - (int64_t)sg.h * per_head);
-        sg.b = find_sequence(t, s.B, key);
+        sg.b = sequence_of(key);
         c_n = t.cu_iters[sg.b + 1] - t.cu_iters[sg.b];
         tile_iter = (int64_t)sg.h * per_head + t.cu_iters[sg.b];
         sg.tile_idx = sg.h * s.B + sg.b;
     } else {
-        const int32_t key = (int32_t)div_iters(s, it, s.Hkv);
-        sg.b = find_sequence(t, s.B, key);
+        const int32_t key = small ? (int32_t)magic_div((uint32_t)it, s.by_heads) : (int32_t)(it / s.Hkv);
+        sg.b = sequence_of(key);
         c_n = t.cu_iters[sg.b + 1] - t.cu_iters[sg.b];
         const int64_t seq_iter = (int64_t)s.Hkv * t.cu_iters[sg.b];
-        sg.h = (int32_t)div_iters(s, it - seq_iter, c_n);
+        if (s.uniform_cn > 0 && small) sg.h = (int32_t)magic_div((uint32_t)(it - seq_iter), s.by_cn);
+        else sg.h = (int32_t)div_iters(s, it - seq_iter, c_n);
         tile_iter = seq_iter + (int64_t)sg.h * c_n;
         sg.tile_idx = sg.b * s.Hkv + sg.h;
     }

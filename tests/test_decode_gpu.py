@@ -120,9 +120,8 @@ def test_result_does_not_depend_on_the_split(group, G):
     plan = la.lean_attn_schedule(seqlens, Hkv * group, Hkv, D, la.BF16, la.KV_PADDED)
     grids = [G] if G else [int(plan.total_iters), int(plan.total_iters) - 1]
     for grid in grids:
-        for remap in (1, 2):
-            got, got_lse, _ = _run(inp, la.Tuning(grid=grid, xcd_remap=remap))
-            _check(got, got_lse, want, want_lse, f"G={grid} remap={remap}")
+        got, got_lse, _ = _run(inp, la.Tuning(grid=grid))
+        _check(got, got_lse, want, want_lse, f"G={grid}")
 
 
 def test_mfma_kernel_on_single_row_groups_matches_valu_kernel_and_oracle():
@@ -269,6 +268,42 @@ def test_waiting_host_gives_up_instead_of_hanging():
     _check(got, got_lse, want, want_lse, "after status")
 
 
+@pytest.mark.parametrize("group", [1, 8])
+def test_delayed_publishers_and_poisoned_partials_never_change_a_bit(group):
+    # The window between StorePartials and Signal (Algorithm 2), and the one before the stores, held open
+    # by sleeping publishers; every partial slot holds NaN before every launch, so a partial read before
+    # its flag, or a flag seen before its partial, shows.  50 launches per (grid, fan-in), all bit-equal.
+    Hkv, D = 2, 128
+    seqlens = [50001, 300]
+    inp = _mk(2, Hkv * group, Hkv, D, "bf16", seqlens, workloads.KV_PADDED, seed=61, outlier=0.01)
+    w = inp.w
+    want, want_lse = _oracle(inp)
+    ws = _workspace(w.B, w.Hq, w.Hkv, w.D, la.BF16)
+    partials = ws[256 + 4 * la.binding.MAX_GRID:].view(torch.float32)
+    delays = ((0, 0, 0), (3, 0, 0), (0, 3, 0), (2, 2, 3), (0, 6, 5))    # (before stores, before flag, every n-th CTA)
+    for grid in (64, 256, 1000, 4096):
+        for fanin in (2, 8, 32, 4096):
+            ref = ref_lse = None
+            for (d_store, d_signal, stride) in delays:
+                tn = la.Tuning(grid=grid, merge_fanin=fanin, debug_delay_store=d_store, debug_delay_signal=d_signal,
+                               debug_delay_stride=stride)
+                for _ in range(10):
+                    partials.fill_(float("nan"))
+                    out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=torch.float32, device="cuda")
+                    lse = torch.full((w.B, w.Hq), float("nan"), dtype=torch.float32, device="cuda")
+                    la.lean_attn_decode(inp.q, inp.k, inp.v, inp.seqlens, out, ws, Hkv=w.Hkv, kv_layout=w.kv_layout,
+                                        kv_seq_stride=w.n_stride, scale=w.scale, lse=lse, tuning=tn)
+                    if ref is None:
+                        torch.cuda.synchronize()
+                        assert la.lean_attn_workspace_status(ws) == 0
+                        ref, ref_lse = out, lse
+                        _check(out.cpu().numpy(), lse.cpu().numpy(), want, want_lse, f"grid={grid} fanin={fanin}")
+                    else:
+                        assert torch.equal(out, ref) and torch.equal(lse, ref_lse), \
+                            f"grid={grid} fanin={fanin} delays={(d_store, d_signal, stride)}: result changed"
+            assert la.lean_attn_workspace_status(ws) == 0
+
+
 @pytest.mark.parametrize("group", [1, 4])
 def test_every_tile_shape_and_merge_fanin(group):
     # two output tiles shared by hundreds of CTAs: deep reduction trees, every compiled LeanTile size
@@ -276,7 +311,7 @@ def test_every_tile_shape_and_merge_fanin(group):
     seqlens = [70001]
     inp = _mk(1, Hkv * group, Hkv, D, "bf16", seqlens, workloads.KV_PADDED, seed=31, outlier=0.01)
     want, want_lse = _oracle(inp)
-    for shape in range(6):
+    for shape in range(7):          # 0: the default of the table, 1..6: every compiled shape
         got, got_lse, _ = _run(inp, la.Tuning(tile_shape=shape))
         _check(got, got_lse, want, want_lse, f"shape={shape}")
     for fanin in (2, 3, 5, 8, 16, 4096):
@@ -293,7 +328,12 @@ def test_head_dim_256_every_tile_shape(dtype, group):
     seqlens = [20011, 515]
     inp = _mk(2, Hkv * group, Hkv, D, dtype, seqlens, workloads.KV_PACKED, seed=41 + group, outlier=0.01)
     want, want_lse = _oracle(inp)
-    for shape in range(6):
+    for shape in range(7):
+        if group > 1 and shape in (1, 3):     # the double-buffered MFMA shapes are not built at D = 256
+            with pytest.raises(la.LeanAttnError) as e:
+                _run(inp, la.Tuning(tile_shape=shape))
+            assert e.value.status == la.binding.ERR_UNSUPPORTED
+            continue
         got, got_lse, _ = _run(inp, la.Tuning(tile_shape=shape))
         _check(got, got_lse, want, want_lse, f"D256 {dtype} g{group} shape={shape}")
     got, got_lse, _ = _run(inp, la.Tuning(grid=1000, merge_fanin=3))
@@ -308,7 +348,7 @@ def test_grid_larger_than_resident(group):
     seqlens = [50000, 3, 120000, 9000]
     inp = _mk(4, Hkv * group, Hkv, D, "bf16", seqlens, workloads.KV_PACKED, seed=32)
     want, want_lse = _oracle(inp)
-    for tn in (dict(grid_multiple=4), dict(grid=4096), dict(grid=3001, merge_fanin=2), dict(grid=4096, xcd_remap=2)):
+    for tn in (dict(grid_multiple=4), dict(grid=4096), dict(grid=3001, merge_fanin=2), dict(grid=4096, merge_fanin=4096)):
         got, got_lse, _ = _run(inp, la.Tuning(**tn))
         _check(got, got_lse, want, want_lse, f"{tn}")
 
@@ -762,8 +802,10 @@ def test_seeded_random_problems_against_the_oracle():
         dtype = "bf16" if r.integers(0, 2) else "f16"
         out_dtype = la.OUT_AS_INPUT if r.integers(0, 3) == 0 else la.OUT_F32
         tn = la.Tuning(grid=int(r.choice([0, 0, 1, 5, 64, 700])), merge_fanin=int(r.choice([0, 0, 2, 5, 4096])),
-                       tile_shape=int(r.integers(0, 6)), ctas_per_cu=int(r.choice([0, 1, 2])),
+                       tile_shape=int(r.integers(0, 7)), ctas_per_cu=int(r.choice([0, 1, 2])),
                        fixed_split=int(r.choice([0, 0, 0, 1, 3])))
+        if D == 256 and tn.tile_shape in (1, 3):
+            tn.tile_shape = 2                         # shapes 1 and 3 of the MFMA core are not built at D = 256
         label = (f"case {case}: D={D} Hkv={Hkv} g={group} N_q={N_q} q_lens={q_lens if ragged_q else None} B={B} "
                  f"seqlens={seqlens} causal={causal} layout={layout} {dtype} out16={out_dtype} grid={tn.grid} "
                  f"fanin={tn.merge_fanin} shape={tn.tile_shape} per_cu={tn.ctas_per_cu} split={tn.fixed_split}")

@@ -13,7 +13,7 @@ import pytest
 import torch
 
 import oracle
-from oracle import lean_alg2, rescale
+from oracle import rescale, stream_k
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_cases.json")
 
@@ -309,18 +309,18 @@ def test_random_unequal_splits_large_dynamic_range():
         assert np.max(np.abs(got - want)) < 1e-11 and abs(got_lse - want_lse) < 1e-11
 
 
-# ---------------------------------------------------------------- Algorithms 1 and 2
+# ---------------------------------------------------------------- the stream-K decomposition (Section 4.3)
 def test_spans_match_the_schedule_of_figure_1():
     # Figure 1 / Section 4.1: 5 SMs, 2 heads, 5 LeanTiles per head: two per CTA;
     # CTA0 and CTA1 take two tiles of head 0, CTA2 one of head 0 and one of head 1.
-    assert lean_alg2.spans(10, 5) == [(0, 2), (2, 4), (4, 6), (6, 8), (8, 10)]
+    assert stream_k.spans(10, 5) == [(0, 2), (2, 4), (4, 6), (6, 8), (8, 10)]
     trace = []
     r = _rng(12)
     T_n, N, D = 4, 20, 4
     q = r.normal(size=(1, 2, D))
     k = r.normal(size=(1, 2, N, D))
     v = r.normal(size=(1, 2, N, D))
-    lean_alg2.lean_attention(q, k, v, [N], Hkv=2, T_n=T_n, G=5, scale=0.5, trace=trace)
+    stream_k.attention_by_spans(q, k, v, [N], Hkv=2, T_n=T_n, G=5, scale=0.5, trace=trace)
     seg = {(t["cta"], t["h"]): t for t in trace}
     assert seg[(0, 0)]["host"] and not seg[(0, 0)]["finishing"]
     assert (seg[(2, 0)]["local_iter"], seg[(2, 0)]["local_iter_end"]) == (4, 5)
@@ -332,16 +332,16 @@ def test_spans_match_the_schedule_of_figure_1():
 def test_grid_formula_example_from_section_4_3():
     # 108 SMs x 2 CTAs per SM = 216; equal tiles per CTA when the count divides
     G = 108 * 2
-    sp = lean_alg2.spans(G * 7, G)
+    sp = stream_k.spans(G * 7, G)
     assert len(sp) == 216 and all(e - s == 7 for s, e in sp)
-    sp = lean_alg2.spans(G * 7 + 5, G)
+    sp = stream_k.spans(G * 7 + 5, G)
     assert [e - s for s, e in sp].count(8) == 5 and sp[-1][1] == G * 7 + 5
-    assert len(lean_alg2.spans(3, 216)) == 3          # never more CTAs than iterations
+    assert len(stream_k.spans(3, 216)) == 3          # never more CTAs than iterations
 
 
 @pytest.mark.parametrize("G", [1, 2, 3, 5, 7, 16, 33, 1000])
 @pytest.mark.parametrize("T_n", [1, 4, 7])
-def test_algorithm_2_equals_exact_attention(G, T_n):
+def test_stream_k_pieces_folded_with_f_equal_exact_attention(G, T_n):
     r = _rng(1000 + G * 10 + T_n)
     B, Hq, Hkv, D = 3, 6, 2, 4
     lens = [23, 1, 10]
@@ -352,7 +352,11 @@ def test_algorithm_2_equals_exact_attention(G, T_n):
     want, want_lse = oracle.decode_attention(q, k, v, lens, Hq=Hq, Hkv=Hkv, D=D, scale=0.6, n_stride=nmax,
                                              dtype=oracle.F64)
     trace = []
-    got, got_lse = lean_alg2.lean_attention(q, k, v, lens, Hkv=Hkv, T_n=T_n, G=G, scale=0.6, trace=trace)
+    got, got_lse = stream_k.attention_by_spans(q, k, v, lens, Hkv=Hkv, T_n=T_n, G=G, scale=0.6, trace=trace)
+    np.testing.assert_allclose(got, want, atol=1e-12)
+    np.testing.assert_allclose(got_lse, want_lse, atol=1e-12)
+    # the pieces of a tile may be folded in any order and bracketing (Section 4.1)
+    got, got_lse = stream_k.attention_by_spans(q, k, v, lens, Hkv=Hkv, T_n=T_n, G=G, scale=0.6, rng=r)
     np.testing.assert_allclose(got, want, atol=1e-12)
     np.testing.assert_allclose(got_lse, want_lse, atol=1e-12)
     # every output tile has exactly one host segment; every iteration is covered once
@@ -368,17 +372,17 @@ def test_algorithm_2_equals_exact_attention(G, T_n):
             assert covered[(b, h)] == math.ceil(lens[b] / T_n)
 
 
-def test_algorithm_2_special_cases_of_section_4_3():
+def test_stream_k_special_cases_of_section_4_3():
     r = _rng(77)
     B, H, D, T_n, N = 2, 3, 4, 4, 32                    # 6 output tiles, 8 iterations each
     q, k, v = r.normal(size=(B, H, D)), r.normal(size=(B, H, N, D)), r.normal(size=(B, H, N, D))
     # grid == number of output tiles: nobody stores a partial (FlashAttention-2 behaviour)
     trace = []
-    lean_alg2.lean_attention(q, k, v, [N, N], Hkv=H, T_n=T_n, G=6, scale=0.5, trace=trace)
+    stream_k.attention_by_spans(q, k, v, [N, N], Hkv=H, T_n=T_n, G=6, scale=0.5, trace=trace)
     assert all(t["host"] and t["finishing"] for t in trace) and len(trace) == 6
     # grid an even multiple: every tile split into the same number of equal parts (fixed split)
     trace = []
-    lean_alg2.lean_attention(q, k, v, [N, N], Hkv=H, T_n=T_n, G=12, scale=0.5, trace=trace)
+    stream_k.attention_by_spans(q, k, v, [N, N], Hkv=H, T_n=T_n, G=12, scale=0.5, trace=trace)
     assert len(trace) == 12 and all(t["local_iter_end"] - t["local_iter"] == 4 for t in trace)
     assert sum(t["host"] for t in trace) == 6
 

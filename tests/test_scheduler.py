@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 import paper_2405_10480_amd as la
-from oracle import lean_alg2
+from oracle import stream_k
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -71,28 +71,59 @@ def test_grid_is_units_times_residency_and_spans_are_equal():
     assert p.total_iters == 8 * math.ceil(262144 / p.T_n)
 
 
+@pytest.mark.parametrize("layout", [la.KV_PADDED, la.KV_PACKED])
 @pytest.mark.parametrize("G", [1, 2, 5, 13, 64, 10_000])
-def test_walk_matches_the_step_by_step_emulation_of_algorithm_2(G):
+def test_walk_matches_the_interval_arithmetic_of_the_decomposition(G, layout):
+    # the span walk the kernel runs (lean_attn_walk is the same code) against the pieces obtained
+    # by intersecting the span intervals with the tile intervals
     Hkv, D = 3, 128
-    seqlens = [700, 1, 0, 257, 3000]
-    p = _plan(seqlens, Hkv, Hkv, D, la.BF16, la.KV_PADDED, num_cus=G, ctas_per_cu=1, grid=G)
-    trace = []
-    r = np.random.default_rng(0)
-    nmax = max(seqlens)
-    q = r.normal(size=(len(seqlens), Hkv, 2))
-    kv = r.normal(size=(len(seqlens), Hkv, nmax, 2))
-    lean_alg2.lean_attention(q, kv, kv, seqlens, Hkv=Hkv, T_n=p.T_n, G=G, scale=1.0, trace=trace)
-    want = {}
-    for t in trace:
-        want.setdefault(t["cta"], []).append(t)
-    assert p.grid == len(lean_alg2.spans(p.total_iters, G))
-    for g in range(p.grid):
-        got = la.lean_attn_walk(p, seqlens, Hkv, la.KV_PADDED, g)
-        ref = sorted(want[g], key=lambda t: (t["b"], t["h"]))
-        assert len(got) == len(ref)
-        for a, b in zip(got, ref):
-            assert (a["b"], a["h"], a["local_iter"], a["local_iter_end"], bool(a["host"]), bool(a["finishing"])) == \
-                   (b["b"], b["h"], b["local_iter"], b["local_iter_end"], b["host"], b["finishing"])
+    for seqlens in ([700, 1, 0, 257, 3000], [640] * 6, [64], [0, 0, 129]):
+        p = _plan(seqlens, Hkv, Hkv, D, la.BF16, layout, num_cus=G, ctas_per_cu=1, grid=G)
+        order = "padded" if layout == la.KV_PADDED else "packed"
+        work = stream_k.pieces(seqlens, Hkv, p.T_n, G, order)
+        stream_k.check_invariants(work, seqlens, Hkv, p.T_n)
+        want = {}
+        for t in work:
+            want.setdefault(t["cta"], []).append(t)
+        assert p.grid == len(stream_k.spans(p.total_iters, G))
+        for g in range(p.grid):
+            got = la.lean_attn_walk(p, seqlens, Hkv, layout, g)
+            ref = want.get(g, [])
+            assert len(got) == len(ref)
+            for a, b in zip(got, ref):
+                assert (a["b"], a["h"], a["local_iter"], a["local_iter_end"], bool(a["host"]), bool(a["finishing"]),
+                        a["last_cta"]) == \
+                       (b["b"], b["h"], b["local_iter"], b["local_iter_end"], b["host"], b["finishing"], b["last_cta"])
+
+
+def test_walk_on_seeded_random_batches_and_grids():
+    # many shapes: the multiply-shift divisions of the walk against plain integer interval arithmetic
+    r = np.random.default_rng(2024)
+    for trial in range(300):
+        B = int(r.integers(1, 9))
+        Hkv = int(r.integers(1, 12))
+        uniform = trial % 3 == 0
+        if uniform:
+            seqlens = [int(r.integers(1, 40000))] * B
+        else:
+            seqlens = [int(x) for x in r.integers(0, 40000, size=B)]
+        if sum(seqlens) == 0:
+            seqlens[0] = 5
+        layout = la.KV_PACKED if trial % 2 else la.KV_PADDED
+        G = int(r.choice([1, 2, 3, 7, 8, 63, 64, 255, 256, 257, 512, 1000, 4096]))
+        p = _plan(seqlens, Hkv, Hkv, 128, la.BF16, layout, num_cus=G, ctas_per_cu=1, grid=G)
+        work = stream_k.pieces(seqlens, Hkv, p.T_n, G, "padded" if layout == la.KV_PADDED else "packed")
+        want = {}
+        for t in work:
+            want.setdefault(t["cta"], []).append(t)
+        probe = sorted(set([0, p.grid - 1, p.grid // 2] + [int(x) for x in r.integers(0, p.grid, size=6)]))
+        for g in probe:
+            got = la.lean_attn_walk(p, seqlens, Hkv, layout, g)
+            ref = want.get(g, [])
+            assert [(a["b"], a["h"], a["local_iter"], a["local_iter_end"], bool(a["host"]), bool(a["finishing"]),
+                     a["last_cta"]) for a in got] == \
+                   [(b["b"], b["h"], b["local_iter"], b["local_iter_end"], b["host"], b["finishing"], b["last_cta"])
+                    for b in ref], (trial, seqlens, Hkv, layout, G, g)
 
 
 def _check_invariants(seqlens, Hkv, layout, p):
@@ -318,6 +349,17 @@ def test_span_invariants_beyond_two_to_the_31_iterations(layout):
     p = _plan(seqlens, 128, 128, 128, la.BF16, layout, num_cus=16, ctas_per_cu=1, grid=16)
     assert p.total_iters > 2 ** 31
     _check_invariants(seqlens, 128, layout, p)
+
+
+@pytest.mark.parametrize("layout", [la.KV_PADDED, la.KV_PACKED])
+@pytest.mark.parametrize("uniform", [False, True])
+def test_span_invariants_just_below_two_to_the_31_iterations(layout, uniform):
+    # the largest iteration spaces the multiply-shift divisions of the walk serve
+    seqlens = [8388607 - (0 if uniform else 64 * (i % 3)) for i in range(256)]
+    for G in (16, 13):
+        p = _plan(seqlens, 63, 63, 128, la.BF16, layout, num_cus=G, ctas_per_cu=1, grid=G)
+        assert 2 ** 31 - 2 ** 26 < p.total_iters < 2 ** 31 - 1
+        _check_invariants(seqlens, 63, layout, p)
 
 
 def test_per_sequence_query_lengths_are_validated():
