@@ -18,12 +18,13 @@
  *
  * One deliberate difference from Algorithm 2: there the host block (the CTA
  * that computed a tile's first LeanTile) merges every peer in a flat loop.
- * Here the CTAs of a tile form a reduction tree (fan-in lean_attn_tuning.
- * merge_fanin) rooted at the FINISHING block, the CTA whose span holds the
- * tile's last LeanTile: it merges last and writes the output.  The operator
- * is associative (Section 4.1), so the result is the same; a CTA then only
- * waits for lower CTA ids.  "host_block" in lean_attn_walk keeps Algorithm 2's
- * meaning (first LeanTile of the tile), it no longer says who reduces.
+ * Here every CTA of a shared tile publishes its partial, and the tile's last
+ * 1..8 CTAs each merge one slice of the tile from all partials and write it
+ * (lean_attn_tuning.merge_fanin selects a reduction tree rooted at the
+ * FINISHING block instead, the CTA whose span holds the tile's last LeanTile).
+ * The operator is associative and commutative (Section 4.1), so the result is
+ * the same.  "host_block" in lean_attn_walk keeps Algorithm 2's meaning (first
+ * LeanTile of the tile), it no longer says who reduces.
  *
  * All pointers named "device" are HIP device pointers on the current device;
  * "host" pointers are ordinary host memory.  No function takes ownership of
@@ -123,10 +124,11 @@ typedef struct lean_attn_tuning {
     int32_t kernel;        /* 0 default, 1 force VALU kernel (needs N_q * Hq == Hkv), 2 force MFMA kernel */
     int32_t reserved_;     /* must be 0 */
     int32_t spin_limit;    /* polls before a waiting CTA gives up and reports PEER_TIMEOUT */
-    int32_t merge_fanin;   /* partials a CTA merges per level of the reduction tree; 0 default (8; 32 for
-                              single-row tiles, which merge a level as wide as the workgroup),
-                              >= LEAN_ATTN_MAX_GRID gives Algorithm 2's flat list: the host block
-                              merges every peer itself */
+    int32_t merge_fanin;   /* 0 default: every CTA of a shared tile publishes its partial and the tile's last
+                              1..8 CTAs each merge one slice of all partials and write it (one level).
+                              >= 2: the reduction is a tree of this fan-in rooted at the finishing block;
+                              >= LEAN_ATTN_MAX_GRID gives Algorithm 2's flat list: one block merges every
+                              peer itself */
     int32_t tile_shape;    /* 0: the library's default for the head dim, dtype and rows per tile (a table filled
                               from the LeanTile sweep); 1..6: a compiled (loads or token blocks per wave, waves
                               per workgroup, buffering) shape, i.e. another LeanTile size T_n: lean_attn_schedule
@@ -184,9 +186,10 @@ typedef struct lean_attn_problem {
 
 /*
  * Bytes of device workspace that suffice for lean_attn_decode on this problem
- * shape whatever the tuning: arrival flags plus one partial (O~[T_m, D], m[T_m],
- * l[T_m]) slot per CTA, as in Algorithm 2 ("Op[g], mp[g], lp[g], flags[g]"),
- * for LEAN_ATTN_MAX_GRID CTAs.  Host-only arithmetic; it does not depend on
+ * shape whatever the tuning: arrival flags plus partial (O~[T_m, D], m[T_m],
+ * l[T_m]) slots as in Algorithm 2 ("Op[g], mp[g], lp[g], flags[g]"), two per CTA
+ * (a span can start inside one shared tile and end inside another), for
+ * LEAN_ATTN_MAX_GRID CTAs.  Host-only arithmetic; it does not depend on
  * the device.  Returns 0 for an unsupported shape.
  */
 size_t lean_attn_workspace_size(int B, int Hq, int Hkv, int D, int dtype);
@@ -196,11 +199,11 @@ size_t lean_attn_problem_workspace_size(const lean_attn_problem* problem);
 
 /*
  * The workspace for launches of at most `max_grid` workgroups (1..LEAN_ATTN_MAX_GRID): a launch
- * needs the flags plus `grid` partial slots, and every entry point checks exactly that against
+ * needs the flags plus 2 x `grid` partial slots, and every entry point checks exactly that against
  * workspace_bytes (LEAN_ATTN_ERR_WORKSPACE otherwise, nothing launched).  The default grid is
  * compute units x 1, or x 2 for batches of many short contexts (lean_attn_plan.grid tells), so a
  * caller that never forces a larger grid can allocate for 2 x the unit count instead of
- * LEAN_ATTN_MAX_GRID (e.g. 8.5 MB instead of 68 MB for 32-row tiles at D = 128 on 256 units).
+ * LEAN_ATTN_MAX_GRID (e.g. 17 MB instead of 136 MB for 32-row tiles at D = 128 on 256 units).
  * Returns 0 for an unsupported problem or grid.
  */
 size_t lean_attn_workspace_size_for_grid(const lean_attn_problem* problem, int max_grid);
@@ -278,7 +281,7 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache,
  * lean_attn_decode for callers that cannot allocate device memory and have no workspace to pass:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, kernels and results as lean_attn_decode, without `workspace` / `workspace_bytes`: the
- * flags and partial slots live in a static device array inside the library (8.5 MB per GPU, held
+ * flags and partial slots live in a static device array inside the library (17.3 MB per GPU, held
  * until the process ends), enough for LEAN_ATTN_STATIC_MAX_GRID workgroups with the largest
  * partial slot.  The default grid (compute units x 1 or x 2) fits on devices of up to 256 units;
  * a launch that needs more slots (a larger device, tuning->grid, grid_multiple or fixed_split

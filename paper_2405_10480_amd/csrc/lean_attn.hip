@@ -22,8 +22,6 @@ static_assert(kMaxGrid == LEAN_ATTN_MAX_GRID, "header and workspace layout disag
 // after an empirical sweep, Section 4.2).
 constexpr int kDefaultCtasPerCu = 1;
 constexpr int kShortContextTokens = 1536;  // mean context at or below which two workgroups share a unit
-constexpr int kDefaultFanin = 8;
-constexpr int kDefaultFaninSingleRow = 32;
 constexpr int kDefaultGridMultiple = 1;
 constexpr int kMaxProbeMode = 6;
 
@@ -64,7 +62,7 @@ static bool pick_variant(int kernel, int dtype, int D, int shape, int T_m, Varia
 
 // Workspace bytes a launch of `grid` workgroups with T_m-row partials touches.
 static size_t workspace_need(int64_t grid, int T_m, int D) {
-    return kPartialsOffset + (size_t)grid * slot_floats(T_m, D) * sizeof(float);
+    return kPartialsOffset + 2 * (size_t)grid * slot_floats(T_m, D) * sizeof(float);  // two slots per workgroup
 }
 
 // Unit count of the device and, per variant, the workgroups that fit on one unit (cached).
@@ -474,9 +472,8 @@ static int build_launch(const lean_attn_problem& p, const void* q, const void* k
     a.delay_stride = tuning ? tuning->debug_delay_stride : 0;
     a.spin_limit = (tuning && tuning->spin_limit > 0) ? tuning->spin_limit : (1 << 22);
     a.has_empty = has_empty;
-    // single-row tiles merge a whole level of up to 32 partials in one round trip (see merge_children_wide)
-    a.fanin = (tuning && tuning->merge_fanin >= 2) ? tuning->merge_fanin
-                                                   : (plan->kernel == 0 ? kDefaultFaninSingleRow : kDefaultFanin);
+    // 0: the default reduction (every CTA publishes, the last few of a tile reduce a slice each)
+    a.fanin = (tuning && tuning->merge_fanin >= 2) ? tuning->merge_fanin : 0;
     a.cta_clock = tuning ? (unsigned long long*)tuning->cta_clock : nullptr;
     a.scale_log2e = p.scale * 1.4426950408889634f;
     return LEAN_ATTN_OK;
@@ -665,10 +662,11 @@ int lean_attn_decode(const void* q, const void* k_cache, const void* v_cache, co
 }
 
 // ---- lean_attn_decode for callers that cannot allocate: the workspace is a static device array ----
-// Partial slots of the largest tile (32 rows at D = 128, 16 at D = 256) for LEAN_ATTN_STATIC_MAX_GRID
-// workgroups plus the flags: 8.5 MB, held by every GPU the library runs on until the process ends.
+// Two partial slots of the largest tile (32 rows at D = 128, 16 at D = 256) for each of
+// LEAN_ATTN_STATIC_MAX_GRID workgroups plus the flags: 17.3 MB, held by every GPU the library runs
+// on until the process ends.
 constexpr size_t kStaticScratchBytes =
-    kPartialsOffset + (size_t)LEAN_ATTN_STATIC_MAX_GRID * 4160 * sizeof(float);
+    kPartialsOffset + 2 * (size_t)LEAN_ATTN_STATIC_MAX_GRID * 4160 * sizeof(float);
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 // In host code `scratch` is only a handle for the runtime's symbol look-up, never an address a
 // kernel may be given: the array's device address is read once per device and kept here.
@@ -708,7 +706,8 @@ int lean_attn_decode_static(const void* q, const void* k_cache, const void* v_ca
     // The array keeps what the last call left.  A call that ran to its end left every flag cleared,
     // one that gave up waiting may not have: the status word and the flags start at zero every time
     // (a fill kernel, not a memset: the call may be under graph capture).
-    const int n = (int)(kPartialsOffset / 4);
+    // (launches from here never exceed LEAN_ATTN_STATIC_MAX_GRID workgroups: only their flag words are used)
+    const int n = (int)((kFlagsOffset + 4 * kFlagWordsPerCta * LEAN_ATTN_STATIC_MAX_GRID) / 4);
     hipLaunchKernelGGL(lean_workspace_clear_kernel, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)hip_stream,
                        (uint32_t*)ws, n);
     if (hipGetLastError() != hipSuccess) return LEAN_ATTN_ERR_HIP;

@@ -13,10 +13,18 @@ constexpr int kDtF16 = 0;
 constexpr int kDtBF16 = 1;
 constexpr int kMaxGrid = 4096;
 
-// Workspace layout (bytes): [0,256) status word, [256, 256+4*kMaxGrid) flags,
-// then kMaxGrid partial slots of slot_floats floats: O~[T_m][D], m[T_m], l[T_m].
+// Workspace layout (bytes): [0,256) status word, then the arrival flags, then the partial slots of
+// slot_floats floats each: O~[T_m][D], m[T_m], l[T_m].
+// A CTA can hold parts of two output tiles that other CTAs share: the one its span starts in the
+// middle of, and the one its span ends in the middle of.  It publishes a partial for each, so
+// every CTA owns two slots: slot 2g for a tile that began in an earlier CTA, slot 2g + 1 for a
+// tile it began itself.  Every slot has kMaxReducers flag words, one per CTA that may read it
+// (each word has exactly one reader, which clears it).
+constexpr int kMaxReducers = 8;
 constexpr size_t kFlagsOffset = 256;
-constexpr size_t kPartialsOffset = kFlagsOffset + 4 * (size_t)kMaxGrid;
+constexpr size_t kFlagWordsPerCta = 2 * kMaxReducers;
+constexpr size_t kPartialsOffset = kFlagsOffset + 4 * kFlagWordsPerCta * (size_t)kMaxGrid;
+__host__ __device__ inline int slot_of(int cta, int first_cta) { return 2 * cta + (cta == first_cta ? 1 : 0); }
 
 inline __host__ __device__ int slot_floats(int T_m, int D) {
     const int n = T_m * (D + 2);
@@ -227,33 +235,63 @@ __device__ __forceinline__ bool debug_delayed(const DecodeArgs& a, int g) {
     return a.delay_stride <= 1 || g % a.delay_stride == a.delay_stride - 1;
 }
 
-// Signal: the barrier waits for every thread's partial stores to be acknowledged.
-__device__ __forceinline__ void signal_arrival(const DecodeArgs& a, int g) {
-    __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): stores acknowledged
+// Signal, once every thread's partial stores are acknowledged (the caller has waited for its own, the
+// barrier collects the workgroup's): one flag word per reader of the slot is set (one store
+// instruction of the first `readers` lanes).
+__device__ __forceinline__ void signal_acknowledged(const DecodeArgs& a, int g, int slot, int readers) {
     __syncthreads();
     if (a.delay_signal && debug_delayed(a, g)) debug_sleep(a.delay_signal);
-    if (threadIdx.x == 0) __hip_atomic_store(a.flags + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((int)threadIdx.x < readers)
+        __hip_atomic_store(a.flags + slot * kMaxReducers + threadIdx.x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void signal_arrival(const DecodeArgs& a, int g, int slot, int readers) {
+    __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): stores acknowledged
+    signal_acknowledged(a, g, slot, readers);
 }
 
-// Wait for `nchild` peers at once: thread j polls the flag of CTA first + j*step.  The wait is
-// bounded twice over, by a poll count and by half a second of wall clock (no output tile takes
-// that long): a peer that never arrives is reported, not waited for.  The consumer clears the
-// flags: each flag has exactly one consumer per launch, so the workspace is clean again when
-// the kernel ends.
+// Poll one flag word until it is set, then clear it (its only reader does).  Bounded twice over, by
+// a poll count and by half a second of wall clock (no output tile takes that long): a peer that
+// never arrives is reported, not waited for.
 constexpr unsigned long long kWaitTicks = 50000000ull;  // 0.5 s of the 100 MHz wall clock
-__device__ __forceinline__ void wait_arrivals(const DecodeArgs& a, int first, int step, int nchild) {
-    if ((int)threadIdx.x < nchild) {
-        uint32_t* flag = a.flags + (first + (int)threadIdx.x * step);
-        const unsigned long long t0 = wall_clock64();
-        int spins = 0;
-        while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-            __builtin_amdgcn_s_sleep(1);
-            if (++spins >= a.spin_limit || ((spins & 255) == 0 && wall_clock64() - t0 > kWaitTicks)) {
-                __hip_atomic_store(a.status, kStatusTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;  // peer never arrived: report, do not hang
-            }
+// `seen`: what an earlier load of the flag returned (0: not set then).
+__device__ __forceinline__ void await_flag(const DecodeArgs& a, uint32_t* flag, uint32_t seen = 0u) {
+    unsigned long long t0 = 0;  // the clock is first read after 256 polls: most waits are over by then
+    int spins = 0;
+    while (seen == 0u && __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+        __builtin_amdgcn_s_sleep(1);
+        ++spins;
+        bool late = false;
+        if ((spins & 255) == 0) {
+            const unsigned long long now = wall_clock64();
+            if (t0 == 0) t0 = now;
+            late = now - t0 > kWaitTicks;
         }
-        __hip_atomic_store(flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (spins >= a.spin_limit || late) {
+            __hip_atomic_store(a.status, kStatusTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;  // peer never arrived: report, do not hang
+        }
+    }
+    __hip_atomic_store(flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// The first poll of a flag, issued but not waited for: the caller's pending partial stores and this
+// load then share one wait (poll_collect), instead of the poll queueing behind the acknowledgements.
+__device__ __forceinline__ uint32_t poll_issue(const uint32_t* flag) {
+    uint32_t v;
+    asm volatile("global_load_dword %0, %1, off sc1" : "=v"(v) : "v"(flag) : "memory");
+    return v;
+}
+__device__ __forceinline__ uint32_t poll_collect(uint32_t v) {
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(v)::"memory");  // every store acknowledged, every poll back
+    return v;
+}
+
+// Tree reduction: wait for `nchild` peers at once, thread j polls the flag of CTA first + j*step
+// (reader 0 of its slot; the tile began in CTA `tile_first`).  The consumer clears the flags: each
+// flag word has exactly one reader per launch, so the workspace is clean again when the kernel ends.
+__device__ __forceinline__ void wait_arrivals(const DecodeArgs& a, int tile_first, int first, int step, int nchild) {
+    if ((int)threadIdx.x < nchild) {
+        const int cta = first + (int)threadIdx.x * step;
+        await_flag(a, a.flags + slot_of(cta, tile_first) * kMaxReducers);
     }
     __syncthreads();  // the partial loads that follow are issued after the flags were seen
 }

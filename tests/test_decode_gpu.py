@@ -279,7 +279,7 @@ def test_delayed_publishers_and_poisoned_partials_never_change_a_bit(group):
     w = inp.w
     want, want_lse = _oracle(inp)
     ws = _workspace(w.B, w.Hq, w.Hkv, w.D, la.BF16)
-    partials = ws[256 + 4 * la.binding.MAX_GRID:].view(torch.float32)
+    partials = ws[256 + 64 * la.binding.MAX_GRID:].view(torch.float32)     # past the status word and the flags
     delays = ((0, 0, 0), (3, 0, 0), (0, 3, 0), (2, 2, 3), (0, 6, 5))    # (before stores, before flag, every n-th CTA)
     for grid in (64, 256, 1000, 4096):
         for fanin in (2, 8, 32, 4096):

@@ -221,10 +221,10 @@ def test_workspace_size_grows_with_the_grid_and_with_the_tile_rows():
     full = la.lean_attn_problem_workspace_size(pr)
     assert la.lean_attn_workspace_size_for_grid(pr, la.binding.MAX_GRID) == full
     assert la.lean_attn_workspace_size(1, 64, 8, 128, la.BF16) == full
-    flags = 256 + 4 * la.binding.MAX_GRID
+    flags = 256 + 4 * 16 * la.binding.MAX_GRID           # status, then 2 slots x 8 reader words per workgroup
     slot = -(-8 * (128 + 2) * 4 // 256) * 256            # (O~[8,128], m[8], l[8]) in fp32, rounded up to 256 bytes
     for g in (1, 256, 512, 4096):
-        assert la.lean_attn_workspace_size_for_grid(pr, g) == flags + g * slot
+        assert la.lean_attn_workspace_size_for_grid(pr, g) == flags + 2 * g * slot
     assert la.lean_attn_workspace_size_for_grid(pr, 0) == 0
     assert la.lean_attn_workspace_size_for_grid(pr, la.binding.MAX_GRID + 1) == 0
     # 33 rows per KV head make two blocks of 17; beyond one launch with per-sequence query lengths a
