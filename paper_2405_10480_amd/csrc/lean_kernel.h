@@ -493,7 +493,7 @@ __device__ __forceinline__ void lean_decode_body(const DecodeArgs& a) {
     int parked_b = 0, parked_h = 0, parked_first = 0, parked_fanin = 2;
     // reducer duties of the default reduction: at most one for the tile the span starts inside and one
     // for the tile it ends inside
-    Duty duty[2];
+    Duty duty_a, duty_b;  // (two named records: an array indexed at run time would live in scratch memory)
     int n_duties = 0;
 
     int64_t it = cta_start;
@@ -565,12 +565,9 @@ __device__ __forceinline__ void lean_decode_body(const DecodeArgs& a) {
                                                  !overlap);
             }
             if (reducer) {
-                duty[n_duties].b = sg.b;
-                duty[n_duties].h = sg.h;
-                duty[n_duties].first_cta = sg.first_cta;
-                duty[n_duties].last_cta = sg.last_cta;
-                duty[n_duties].own_parked = sole;
-                duty[n_duties].signal_pending = overlap;
+                const Duty d = {sg.b, sg.h, sg.first_cta, sg.last_cta, sole, overlap};
+                if (n_duties == 0) duty_a = d;
+                else duty_b = d;
                 ++n_duties;
             }
         } else {
@@ -606,8 +603,8 @@ __device__ __forceinline__ void lean_decode_body(const DecodeArgs& a) {
         }
         reduce_tile<Core, CPT, F>(a, own, g, parked_b, parked_h, parked_first, g, parked_fanin, merge_scratch);
     }
-    for (int i = 0; i < n_duties; ++i)
-        reduce_slice<Core, THREADS>(a, duty[i], g, merge_scratch, parked_o, parked_m, parked_l);
+    if (n_duties > 0) reduce_slice<Core, THREADS>(a, duty_a, g, merge_scratch, parked_o, parked_m, parked_l);
+    if (n_duties > 1) reduce_slice<Core, THREADS>(a, duty_b, g, merge_scratch, parked_o, parked_m, parked_l);
     stamp(a, g, kClkExit);
 }
 
