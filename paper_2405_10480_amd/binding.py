@@ -79,15 +79,19 @@ _lib = None
 
 
 def library_path() -> str:
-    return _build.LIBRARY
+    """The shared library this binding loads: the in-tree build, or the file named by LEAN_ATTN_LIBRARY
+    (for comparing two builds of the library on one machine)."""
+    return os.environ.get("LEAN_ATTN_LIBRARY") or _build.LIBRARY
 
 
 def _load():
     global _lib
     if _lib is not None:
         return _lib
-    path = _build.LIBRARY
+    path = library_path()
     if not os.path.exists(path):
+        if path != _build.LIBRARY:
+            raise FileNotFoundError(path)
         _build.build()
     lib = ctypes.CDLL(path)
     vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
