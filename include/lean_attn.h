@@ -82,6 +82,7 @@ typedef enum lean_attn_kv_layout { LEAN_ATTN_KV_PADDED = 0, LEAN_ATTN_KV_PACKED 
 #define LEAN_ATTN_MAX_QUERY_ROWS 256  /* N_q * Hq / Hkv: query rows that share one KV head */
 #define LEAN_ATTN_MAX_GRID 4096  /* upper bound on workgroups; sizes the workspace */
 #define LEAN_ATTN_STATIC_MAX_GRID 512  /* workgroups per launch of lean_attn_decode_static */
+#define LEAN_ATTN_NUM_TILE_SHAPES 9  /* lean_attn_tuning.tile_shape runs 1..9; not every shape exists for every core */
 
 /*
  * The stream-K schedule of one call (Section 4.3 and the first lines of
@@ -108,7 +109,7 @@ typedef struct lean_attn_plan {
     int32_t fixed_split;      /* 0: stream-K spans; s >= 1: baseline schedule, s parts per output tile,
                                  CTA g = tile_idx*s + part, grid = num_output_tiles*s */
     int32_t C_m;              /* row blocks per KV head */
-    int32_t tile_shape;       /* the compiled tile shape used, 1..6 (lean_attn_tuning.tile_shape, or the library's
+    int32_t tile_shape;       /* the compiled tile shape used, 1..9 (lean_attn_tuning.tile_shape, or the library's
                                  default for this head dim, dtype and T_m) */
 } lean_attn_plan;
 
@@ -131,8 +132,10 @@ typedef struct lean_attn_tuning {
                               peer itself */
     int32_t tile_shape;    /* 0: the library's default for the head dim, dtype and rows per tile (a table filled
                               from the LeanTile sweep); 1..6: a compiled (loads or token blocks per wave, waves
-                              per workgroup, buffering) shape, i.e. another LeanTile size T_n: lean_attn_schedule
-                              reports T_n and the shape used */
+                              per workgroup, buffering) shape, i.e. another LeanTile size T_n; 7..9: shapes of
+                              the matrix-core kernels that stage K and V in LDS (D = 128: all three, D = 256:
+                              7 and 8); a shape that is not built gives LEAN_ATTN_ERR_UNSUPPORTED.
+                              lean_attn_schedule reports T_n and the shape used */
     int32_t grid_multiple; /* default G = units x ctas_per_cu x grid_multiple (0: library default) */
     int32_t fixed_split;   /* 0: LeanAttention's stream-K spans.  Baseline schedules of Sections 3.3 / 4.3:
                               s >= 1 cuts every output tile into s near-equal parts (s = 1: no split,

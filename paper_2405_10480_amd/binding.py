@@ -22,6 +22,7 @@ OK = 0
 ERR_NULL_POINTER, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE = -1, -2, -3, -4
 ERR_SEQLEN, ERR_BATCH_TOO_LARGE, ERR_HIP, ERR_TUNING, ERR_PEER_TIMEOUT, ERR_STATIC_LIMIT = -5, -6, -7, -8, -9, -10
 STATIC_MAX_GRID = 512
+NUM_TILE_SHAPES = 9
 
 
 class Plan(ctypes.Structure):

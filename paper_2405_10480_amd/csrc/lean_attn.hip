@@ -34,15 +34,21 @@ static int max_tile_rows(int D) { return D <= 128 ? LEAN_ATTN_MAX_TILE_ROWS : 16
 static int row_class(int T_m) { return T_m <= 1 ? 0 : T_m <= 8 ? 1 : T_m <= 16 ? 2 : 3; }
 
 // Default tile shape (1..kNumShapes, see lean_kernels.hip for what each number builds) per
-// [dtype f16, bf16][head dim 64, 128, 256][row class].  With non-temporal loads the memory system
-// runs fastest with about 8 KiB in flight per wave and one four-wave workgroup per compute unit,
-// single-buffered: shape 6 (T_n = 64 tokens at D = 128) for single rows and for one row block at
-// D = 128.  The MFMA core's bytes in flight scale with the row length, so it takes eight waves at
-// D = 64 (shape 4) and two token blocks per wave at D = 256 (shape 5); two row blocks take two
-// token blocks per wave (shape 5; double-buffered, shape 1, at D = 64).
+// [dtype f16, bf16][head dim 64, 128, 256][row class], filled from the LeanTile sweep at 1 GiB of
+// K/V per call (the sweep of Section 4.2, here `bench.py --tile-sweep`).  With non-temporal loads the
+// memory system runs fastest with about 32 KiB in flight per compute unit, single-buffered:
+//   * one row (VALU core) and one row block at D = 128: four waves with 8 KiB each, shape 6
+//     (T_n = 64 tokens at D = 128) -- 6 % ahead of every other shape at 2..16 rows;
+//   * D = 64, where a 16-token block is only 4 KiB of K and V: eight waves (shape 4) up to 8 rows,
+//     two blocks per wave (shape 5) for 9..16;
+//   * D = 256: two token blocks per wave (shape 5);
+//   * two row blocks: a step's arithmetic is about twice as long, and four waves no longer cover
+//     each other's load latency: eight waves, next step's loads issued early (shape 4) at D = 128,
+//     the double-buffered shape 1 at D = 64.
+// Both dtypes measure alike; they keep separate rows because the table is keyed on them.
 static const int8_t kDefaultShape[2][3][4] = {
-    /* f16  */ {{6, 4, 4, 1}, {6, 6, 6, 5}, {6, 5, 5, 0}},
-    /* bf16 */ {{6, 4, 4, 1}, {6, 6, 6, 5}, {6, 5, 5, 0}},
+    /* f16  */ {{6, 4, 5, 1}, {6, 6, 6, 4}, {6, 5, 5, 0}},
+    /* bf16 */ {{6, 4, 5, 1}, {6, 6, 6, 4}, {6, 5, 5, 0}},
 };
 
 // kernel: 0 VALU single-row core, 1 MFMA query-group core; T_m: query rows per output tile;

@@ -7,6 +7,7 @@
 
 #include "lean_device.h"
 #include "lean_gqa_core.h"
+#include "lean_gqa_lds_core.h"
 #include "lean_kernel.h"
 #include "lean_mha_core.h"
 #include "lean_variants.h"
@@ -54,8 +55,20 @@ static Variant shape_of(int shape) {
         case 4: return variant_of<GqaCore<DT, D, 1, 8, false>, true>();
         case 5: return variant_of<GqaCore<DT, D, 2, 4, false>, true>();
         case 6: return variant_of<GqaCore<DT, D, 1, 4, false>, true>();
-        default: return kNone;
+        default: break;
     }
+    // K/V staged in LDS by direct loads: <blocks per wave per step, waves, stages>.  Measured on the
+    // 256-unit part they stream 0-4 % slower than the register shapes above (the loads that stay in
+    // flight across the arithmetic are more than the memory system needs), so no default uses them.
+    if constexpr (D >= 128) {
+        switch (shape) {
+            case 7: return variant_of<GqaLdsCore<DT, D, 256 / D, 4, 2>>();
+            case 8: if constexpr (D == 128) return variant_of<GqaLdsCore<DT, D, 1, 8, 2>>(); else return variant_of<GqaLdsCore<DT, D, 1, 2, 2>>();
+            case 9: if constexpr (D == 128) return variant_of<GqaLdsCore<DT, D, 1, 4, 2>>(); else break;
+            default: break;
+        }
+    }
+    return kNone;
 }
 #else
 // two blocks of 16 query rows per pass over K/V (17..32 rows per output tile, D <= 128)
@@ -64,11 +77,20 @@ static Variant shape_of(int shape) {
     switch (shape) {
         case 1: return variant_of<GqaCore<DT, D, 2, 4, true, 2>, true>();
         case 2: return variant_of<GqaCore<DT, D, 1, 4, true, 2>>();
-        case 3: case 4: return variant_of<GqaCore<DT, D, 1, 8, false, 2>>();
-        case 5: return variant_of<GqaCore<DT, D, 2, 4, false, 2>, true>();
+        case 3: case 4: return variant_of<GqaCore<DT, D, 1, 8, false, 2>, true>();
+        case 5: return variant_of<GqaCore<DT, D, 2, 4, false, 2>>();
         case 6: return variant_of<GqaCore<DT, D, 1, 4, false, 2>>();
-        default: return kNone;
+        default: break;
     }
+    if constexpr (D == 128) {
+        switch (shape) {
+            case 7: return variant_of<GqaLdsCore<DT, D, 2, 4, 2, 2>>();
+            case 8: return variant_of<GqaLdsCore<DT, D, 1, 8, 2, 2>>();
+            case 9: return variant_of<GqaLdsCore<DT, D, 1, 4, 2, 2>>();
+            default: break;
+        }
+    }
+    return kNone;
 }
 #endif
 

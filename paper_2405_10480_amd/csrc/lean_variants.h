@@ -6,10 +6,11 @@
 //   MFMA core:  NBLK blocks of 16 tokens per wave per step, NW waves; T_n = NW * NBLK * 16.
 //               One (T_m <= 16) or two (T_m <= 32, D <= 128) blocks of 16 query rows per pass.
 #pragma once
+#include "../../include/lean_attn.h"
 
 namespace lean {
 
-constexpr int kNumShapes = 6;  // compiled tile shapes per (family, dtype, head dim), numbered 1..6
+constexpr int kNumShapes = LEAN_ATTN_NUM_TILE_SHAPES;  // tile shapes per (family, dtype, head dim), numbered 1..9 (not every one is built for every family)
 
 struct Variant {
     const void* fn;           // arguments by value (null: no such variant)

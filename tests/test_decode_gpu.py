@@ -69,6 +69,17 @@ def _check(got, got_lse, want, want_lse, label=""):
     return max_abs, rel_l2
 
 
+N_SHAPES = 9
+
+
+def _built(rows, D, shape):
+    """Which tile shapes exist: 1..6 everywhere but the double-buffered MFMA shapes at D = 256;
+    7..9 (K/V staged in LDS) for the MFMA cores at D = 128, 7 and 8 at D = 256."""
+    if shape <= 6:
+        return not (rows > 1 and D == 256 and shape in (1, 3))
+    return rows > 1 and (D == 128 or (D == 256 and shape in (7, 8)))
+
+
 def _mk(B, Hq, Hkv, D, dtype, seqlens, layout, seed, outlier=0.0):
     w = workloads.Workload(f"t_b{B}_h{Hq}_{Hkv}_d{D}_{dtype}", B, Hq, Hkv, D, dtype, tuple(seqlens), layout,
                            seed=seed, outlier_frac=outlier)
@@ -311,7 +322,12 @@ def test_every_tile_shape_and_merge_fanin(group):
     seqlens = [70001]
     inp = _mk(1, Hkv * group, Hkv, D, "bf16", seqlens, workloads.KV_PADDED, seed=31, outlier=0.01)
     want, want_lse = _oracle(inp)
-    for shape in range(7):          # 0: the default of the table, 1..6: every compiled shape
+    for shape in range(N_SHAPES + 1):          # 0: the default of the table, then every compiled shape
+        if not _built(group, D, shape):
+            with pytest.raises(la.LeanAttnError) as e:
+                _run(inp, la.Tuning(tile_shape=shape))
+            assert e.value.status == la.binding.ERR_UNSUPPORTED
+            continue
         got, got_lse, _ = _run(inp, la.Tuning(tile_shape=shape))
         _check(got, got_lse, want, want_lse, f"shape={shape}")
     for fanin in (2, 3, 5, 8, 16, 4096):
@@ -328,8 +344,8 @@ def test_head_dim_256_every_tile_shape(dtype, group):
     seqlens = [20011, 515]
     inp = _mk(2, Hkv * group, Hkv, D, dtype, seqlens, workloads.KV_PACKED, seed=41 + group, outlier=0.01)
     want, want_lse = _oracle(inp)
-    for shape in range(7):
-        if group > 1 and shape in (1, 3):     # the double-buffered MFMA shapes are not built at D = 256
+    for shape in range(N_SHAPES + 1):
+        if not _built(group, D, shape):
             with pytest.raises(la.LeanAttnError) as e:
                 _run(inp, la.Tuning(tile_shape=shape))
             assert e.value.status == la.binding.ERR_UNSUPPORTED
@@ -554,7 +570,8 @@ def test_query_tiles_deep_trees_any_split_and_tile_shape(N_q, group):
                    outlier=0.01)
     want, want_lse = _oracle_attend(inp)
     for tn in (la.Tuning(), la.Tuning(grid=3), la.Tuning(grid=1000, merge_fanin=3), la.Tuning(fixed_split=5),
-               la.Tuning(tile_shape=1), la.Tuning(tile_shape=4), la.Tuning(tile_shape=5, ctas_per_cu=2)):
+               la.Tuning(tile_shape=1), la.Tuning(tile_shape=4), la.Tuning(tile_shape=5, ctas_per_cu=2),
+               la.Tuning(tile_shape=7), la.Tuning(tile_shape=8, grid=700), la.Tuning(tile_shape=9, fixed_split=3)):
         got, got_lse = _run_attend(inp, tn)
         _check(got.cpu().numpy(), got_lse, want, want_lse, f"N_q={N_q} g={group} grid={tn.grid} shape={tn.tile_shape}")
 
@@ -802,10 +819,10 @@ def test_seeded_random_problems_against_the_oracle():
         dtype = "bf16" if r.integers(0, 2) else "f16"
         out_dtype = la.OUT_AS_INPUT if r.integers(0, 3) == 0 else la.OUT_F32
         tn = la.Tuning(grid=int(r.choice([0, 0, 1, 5, 64, 700])), merge_fanin=int(r.choice([0, 0, 2, 5, 4096])),
-                       tile_shape=int(r.integers(0, 7)), ctas_per_cu=int(r.choice([0, 1, 2])),
+                       tile_shape=int(r.integers(0, N_SHAPES + 1)), ctas_per_cu=int(r.choice([0, 1, 2])),
                        fixed_split=int(r.choice([0, 0, 0, 1, 3])))
-        if D == 256 and tn.tile_shape in (1, 3):
-            tn.tile_shape = 2                         # shapes 1 and 3 of the MFMA core are not built at D = 256
+        if not _built(N_q * group, D, tn.tile_shape):
+            tn.tile_shape = 2
         label = (f"case {case}: D={D} Hkv={Hkv} g={group} N_q={N_q} q_lens={q_lens if ragged_q else None} B={B} "
                  f"seqlens={seqlens} causal={causal} layout={layout} {dtype} out16={out_dtype} grid={tn.grid} "
                  f"fanin={tn.merge_fanin} shape={tn.tile_shape} per_cu={tn.ctas_per_cu} split={tn.fixed_split}")
