@@ -30,9 +30,15 @@
 // a token, lane group g a 16-byte piece of each quarter row); loading that pattern
 // straight from memory reads 16-byte pieces strided over 16 rows and streams at only
 // 6.0 instead of 7.1 TB/s on this machine, so the K tile of a wave takes a detour
-// through a wave-private LDS area (padded rows, conflict-free both ways, no barrier:
-// the LDS queue of a wave is in order).  V goes from global memory straight to the
-// MFMA operand registers.
+// through a wave-private LDS area (rows padded to 272 bytes, no barrier: the LDS queue of a
+// wave is in order).  The staging stores are conflict-free.  The operand reads (16 rows at
+// the 272-byte stride per lane group) take twice the LDS cycles of a linear wave-wide
+// 16-byte read, measured with SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE on the isolated
+// patterns: store 2 units, read 1 + 1 conflict unit, i.e. the ratio 0.25 the kernel shows;
+// an XOR swizzle of unpadded rows measures the same, unpadded rows 8 units.  LDS
+// instructions are issued in under 4 % of the wave cycles of this HBM-bound loop, so the
+// read pattern is left as it is.  V goes from global memory straight to the MFMA operand
+// registers.
 #pragma once
 #include "lean_device.h"
 

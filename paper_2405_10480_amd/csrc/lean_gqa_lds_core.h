@@ -12,8 +12,9 @@
 //   K: the KiB holds whole rows; the 16-byte chunk c of row t is stored at chunk position
 //      c ^ (t % 16) of its row.  The A operand of S^T = K Q^T (lane r: token 4*(r%4) + r/4,
 //      lane group g: chunk 4*c2 + g) is then read with ds_read_b128 from 16 rows at 16 different
-//      chunk positions: conflict-free, and no staging store.  Every row is still fetched as one
-//      contiguous run of 256 (D = 128) or 512 bytes.
+//      chunk positions, and there is no staging store (measured: the read costs what the read
+//      from GqaCore's padded rows costs, twice a linear one).  Every row is still fetched as
+//      one contiguous run of 256 (D = 128) or 512 bytes.
 //   V: lane (m, g) fetches what GqaCore loads into registers (row 4*j + g, 16 bytes at m * 16 of
 //      each 256-byte piece of the row) and reads back its own slot: LDS is a queue per lane.
 //

@@ -497,12 +497,12 @@ def test_widened_named_workloads_full_size(idx):
 
 
 def test_ragged_batch_full_size_sampled_heads():
-    # 17 GB of cache: the oracle checks every sequence for a seeded sample of KV heads
+    # 21 GB of cache: the oracle checks every sequence for a seeded sample of 8 of the 32 KV heads
     w = workloads.named(4)
     inp = workloads.generate(w, device="cuda")
     got, got_lse, _ = _run(inp)
     assert np.all(np.isfinite(got))
-    heads = sorted(np.random.default_rng(4).choice(w.Hkv, size=3, replace=False).tolist())
+    heads = sorted(np.random.default_rng(4).choice(w.Hkv, size=8, replace=False).tolist())
     for h in heads:
         sub = workloads.Workload("sub", w.B, 1, 1, w.D, w.dtype, w.seqlens, workloads.KV_PACKED)
         want, want_lse = oracle.decode_attention(inp.q[:, h:h + 1].contiguous(), inp.k[h:h + 1], inp.v[h:h + 1],

@@ -540,3 +540,13 @@ def test_ragged_query_lengths_reduce_to_the_uniform_and_single_sequence_forms():
         start += q_lens[b]
     with pytest.raises(ValueError):   # causal: more query rows than cached tokens
         oracle.attention_ragged(r.normal(size=(13, Hq, D)), k, v, lens, [2, 5, 6], **kw)
+
+
+def test_error_metrics_on_known_vectors():
+    # hand-computed: got - want = (0, 0, 0.5, -2) -> max |.| = 2, ||diff|| = sqrt(4.25), ||want|| = sqrt(1+4+9+16)
+    max_abs, rel_l2 = oracle.error_metrics([1.0, 2.0, 3.5, 2.0], [1.0, 2.0, 3.0, 4.0])
+    assert max_abs == 2.0 and rel_l2 == pytest.approx(math.sqrt(4.25 / 30.0), rel=1e-15)
+    # identical inputs: both zero; a zero reference reports the absolute norm instead of dividing by zero
+    assert oracle.error_metrics([[3.0, -4.0]], [[3.0, -4.0]]) == (0.0, 0.0)
+    assert oracle.error_metrics([3.0, -4.0], [0.0, 0.0]) == (4.0, 5.0)
+    assert oracle.error_metrics([], []) == (0.0, 0.0)

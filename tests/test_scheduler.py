@@ -458,3 +458,28 @@ def test_prepare_writes_a_launch_block_whose_grid_does_not_depend_on_the_lengths
     with pytest.raises(la.LeanAttnError) as e:
         la.lean_attn_attend_prepare(_problem(300, 1, 16, 2, 128, stride=8), q, k, v, [5] * 300, out, ws, block, tuning=tn)
     assert e.value.status == -6
+
+
+def test_default_tile_shapes_are_the_ones_the_committed_sweep_supports():
+    # The (head dim, dtype, rows per tile) -> shape table of the library against the committed summary of
+    # `bench.py --tile-sweep`: the table's pick is the sweep's default column, and it is within 3 % of the
+    # fastest variant of its case (any shape, one or two workgroups per unit).
+    path = os.path.join(ROOT, "profiles", "tile_sweep_1GiB_per_call.md")
+    rows = [[c.strip() for c in line.strip().strip("|").split("|")] for line in open(path)
+            if re.match(r"^\|\s*\d+\s*\|", line)]
+    assert len(rows) == 22        # 3 head dims x 2 dtypes x {1, 8, 16, 32} rows, no 32-row tiles at D = 256
+    classes = set()
+    for D, dtype, n_rows, shape, default_us, _best, best_us, _ratio in rows:
+        D, n_rows, shape = int(D), int(n_rows), int(shape)
+        code = la.F16 if dtype == "f16" else la.BF16
+        ctx = (1 << 30) // (8 * D * 2 * 2)
+        p = _plan([ctx], 8 * n_rows, 8, D, code, la.KV_PADDED, num_cus=256)
+        assert p.tile_shape == shape, f"D={D} {dtype} rows={n_rows}: library picks {p.tile_shape}, sweep file says {shape}"
+        assert p.T_m == n_rows and p.kernel == (0 if n_rows == 1 else 1)
+        assert float(default_us) <= 1.03 * float(best_us), f"D={D} {dtype} rows={n_rows}: default is not near the best"
+        classes.add((D, dtype, 0 if n_rows == 1 else 1 if n_rows <= 8 else 2 if n_rows <= 16 else 3))
+    assert len(classes) == 22     # every cell of the table is covered once
+    # the class boundaries: 2..8, 9..16 and 17..32 rows share a default each
+    for D, lo, hi in ((64, 9, 16), (128, 17, 32), (64, 2, 8)):
+        picks = {_plan([4096], 4 * r, 4, D, la.BF16, la.KV_PADDED, num_cus=256).tile_shape for r in range(lo, hi + 1)}
+        assert len(picks) == 1
