@@ -195,6 +195,7 @@ class Bench:
                          "note": "same kernels and fused reduction, only the schedule differs; prepared calls, "
                                  "back to back under one event pair, median of 3 rounds"}
 
+        balance = self.span_balance(w, inp, ks, vs, out, ws, tuning, int(plan.grid), copies)
         traffic, traffic_source = _traffic_from_profiles(w.name)
         res = {
             "workload": w.name, "kv_bytes": one_copy,
@@ -207,6 +208,7 @@ class Bench:
             "query_rows_per_tile": int(plan.T_m), "iters": int(plan.total_iters), "cache_copies_rotated": copies,
             "traffic": traffic, "traffic_source": traffic_source,
             "schedule_comparison": schedules,
+            "span_balance": balance,
         }
         config = {"workload": w.name, "B": w.B, "N_q": w.N_q, "causal": bool(w.causal), "Hq": w.Hq, "Hkv": w.Hkv,
                   "D": w.D, "query_rows_per_tile": int(plan.T_m), "tiles_per_kv_head": int(plan.C_m),
@@ -220,6 +222,41 @@ class Bench:
         del ks, vs, steps_prepared, inp
         t.cuda.empty_cache()
         return res, config, extra, w
+
+    def span_balance(self, w, inp, ks, vs, out, ws, tuning, grid, copies):
+        """When the workgroups finish streaming their equal spans (Section 4.3), from the library's per-CTA
+        clock trace (lean_attn_tuning.cta_clock: 16 words per workgroup at 100 MHz; word 0 kernel entry,
+        word 1 end of the span loop, word 3 exit).  Microseconds after the first workgroup entered."""
+        t, la = self.torch, self.la
+        if w.N_q != 1:
+            return None
+        import numpy as np
+        clk = t.zeros(16 * grid, dtype=t.int64, device=self.dev)
+        tn = la.Tuning(grid=tuning.grid, ctas_per_cu=tuning.ctas_per_cu, tile_shape=tuning.tile_shape)
+        tn.cta_clock = clk.data_ptr()
+        ends, exits = [], []
+        for i in range(2 + 6):
+            j = i % copies
+            clk.zero_()
+            la.lean_attn_decode(inp.q, ks[j], vs[j], inp.seqlens, out.view(w.B, w.Hq, w.D), ws, Hkv=w.Hkv,
+                                kv_layout=w.kv_layout, kv_seq_stride=w.n_stride, scale=w.scale, tuning=tn)
+            t.cuda.synchronize()
+            c = clk.cpu().numpy().reshape(grid, 16).astype(np.float64)
+            if i >= 2:
+                t0 = c[:, 0].min()
+                ends.append((c[:, 1] - t0) / 100.0)
+                exits.append((c[:, 3] - t0) / 100.0)
+        end = np.mean(ends, axis=0)
+        last = float(np.mean([e.max() for e in ends]))
+        by_xcd = [round(float(np.mean([e.max() - e[x::8].mean() for e in ends])), 2) for x in range(min(8, grid))]
+        return {"span_loop_end_us": {"first": round(float(np.mean([e.min() for e in ends])), 2),
+                                     "median": round(float(np.median(end)), 2), "last": round(last, 2)},
+                "kernel_end_us": round(float(np.mean([e.max() for e in exits])), 2),
+                "mean_lead_over_last_us": round(float(np.mean([e.max() - e.mean() for e in ends])), 2),
+                "mean_lead_by_workgroup_id_mod_8_us": by_xcd,
+                "note": "per-CTA clock trace of 6 launches (the trace adds a few stores per workgroup); workgroup "
+                        "i runs on XCD i mod 8 on the default stream; lead = how long before the last workgroup a "
+                        "workgroup left its span loop"}
 
     def headline_extras(self, w, inp, ks, vs, steps_prepared, prepared, tuning, ws, one_copy, copies):
         t, la, args = self.torch, self.la, self.args
@@ -553,6 +590,7 @@ def main() -> int:
                    "hbm_bytes": props.total_memory},
         "stream_read_probe_GBps": extra.get("stream_read_probe_GBps"),
         "schedule_comparison": res["schedule_comparison"],
+        "span_balance": res["span_balance"],
         "paper_context": "LeanAttention reports speedups over FlashDecoding only (avg 1.73x, up to 2.18x at 256k, "
                          "A100-80GB, FP16->FP32); no absolute number for this metric",
     }
