@@ -736,8 +736,8 @@ const char* lean_attn_strerror(int status) {
         case LEAN_ATTN_OK: return "ok";
         case LEAN_ATTN_ERR_NULL_POINTER: return "a required pointer is null";
         case LEAN_ATTN_ERR_BAD_SHAPE: return "bad shape: B, N_q, Hq, Hkv must be positive, Hq a multiple of Hkv, at most 256 query rows per KV head, 16-byte aligned tensors";
-        case LEAN_ATTN_ERR_UNSUPPORTED: return "unsupported head dim (64, 128, 256), dtype (f16, bf16), output type or layout";
-        case LEAN_ATTN_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or too small for the flags and one partial slot per workgroup of the launch";
+        case LEAN_ATTN_ERR_UNSUPPORTED: return "unsupported head dim (64, 128, 256), dtype (f16, bf16), output type, layout, or a tile shape that is not built for this core and head dim";
+        case LEAN_ATTN_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or too small for the flags and two partial slots per workgroup of the launch";
         case LEAN_ATTN_ERR_SEQLEN: return "negative sequence length, padded stride below the longest sequence, or more than 2^31 tokens";
         case LEAN_ATTN_ERR_BATCH_TOO_LARGE: return "batch larger than LEAN_ATTN_MAX_BATCH";
         case LEAN_ATTN_ERR_HIP: return "a HIP runtime call failed";

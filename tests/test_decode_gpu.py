@@ -191,7 +191,7 @@ def test_error_paths_launch_nothing():
 
 
 def test_workspace_sized_for_the_launch_grid_and_checked_per_launch():
-    # the flags plus one partial slot per workgroup of the launch is all a call needs; one slot less is
+    # the flags plus two partial slots per workgroup of the launch are all a call needs; one workgroup less is
     # an error and nothing is launched
     inp = _mk(1, 16, 2, 128, "bf16", [40000], workloads.KV_PADDED, seed=5)
     w = inp.w

@@ -483,3 +483,22 @@ def test_default_tile_shapes_are_the_ones_the_committed_sweep_supports():
     for D, lo, hi in ((64, 9, 16), (128, 17, 32), (64, 2, 8)):
         picks = {_plan([4096], 4 * r, 4, D, la.BF16, la.KV_PADDED, num_cus=256).tile_shape for r in range(lo, hi + 1)}
         assert len(picks) == 1
+
+
+def test_binding_constants_match_the_header():
+    header = open(os.path.join(ROOT, "include", "lean_attn.h")).read()
+
+    def define(name):
+        return int(re.search(rf"#define {name}\s+(-?\d+)", header).group(1))
+
+    assert define("LEAN_ATTN_NUM_TILE_SHAPES") == la.NUM_TILE_SHAPES
+    assert define("LEAN_ATTN_STATIC_MAX_GRID") == la.binding.STATIC_MAX_GRID
+    # a shape number past the last one is a tuning error, a shape that is not built for the core is "unsupported"
+    with pytest.raises(la.LeanAttnError) as e:
+        _plan([4096], 8, 8, 128, la.BF16, la.KV_PADDED, num_cus=256, tile_shape=la.NUM_TILE_SHAPES + 1)
+    assert e.value.status == la.binding.ERR_TUNING
+    with pytest.raises(la.LeanAttnError) as e:
+        _plan([4096], 8, 8, 128, la.BF16, la.KV_PADDED, num_cus=256, tile_shape=7)   # single-row core: shapes 1..6
+    assert e.value.status == la.binding.ERR_UNSUPPORTED
+    assert _plan([4096], 64, 8, 128, la.BF16, la.KV_PADDED, num_cus=256, tile_shape=7).T_n == 128
+    assert _plan([4096], 64, 8, 256, la.BF16, la.KV_PADDED, num_cus=256, tile_shape=8).T_n == 32
