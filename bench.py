@@ -16,7 +16,9 @@ contexts 4k .. 256k at batch 1 and 4.  ``--workload N`` measures only that one
 Successive steps rotate over distinct copies of the cache so that no step finds
 its K/V in the 256 MB last-level cache.
 
-Timing of a configuration: W warm-up steps, then exactly K steps enqueued back
+Timing of a configuration: an untimed clock ramp (40 ms of the same launches:
+after an idle gap the first launches run 5-10 % slower until the clocks are back
+up), W warm-up steps, then exactly K steps enqueued back
 to back between two synchronisations (``ms_per_step``, ``value``), with one HIP
 event pair around them on the launch stream (``roofline.achieved`` = algorithmic
 bytes / average launch duration).  A separate pass times K single launches, each
@@ -36,6 +38,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 LLC_BYTES = 256 << 20           # Infinity Cache
+RAMP_MS = 40.0                  # untimed sustained load before a timed region (clock ramp after idle)
 HEADLINE = 4                    # the largest single-GPU configuration of the five
 
 
@@ -92,6 +95,21 @@ class Bench:
             got.append(a.elapsed_time(b) / reps)
         return sorted(got)[len(got) // 2]
 
+    def ramp(self, calls, ms: float = RAMP_MS):
+        """Keep the GPU busy with `calls` for `ms` milliseconds, untimed.  After an idle gap (input
+        generation, a host-side pause) the first launches run 5-10 % slower until the clocks are back up
+        (measured: about 15 ms of sustained load); every timed region starts after such a ramp so that it
+        measures the steady state a decode loop runs in."""
+        t = self.torch
+        t0 = time.perf_counter()
+        i = 0
+        while (time.perf_counter() - t0) * 1e3 < ms:
+            for _ in range(16):
+                calls[i % len(calls)]()
+                i += 1
+            t.cuda.synchronize()
+        return i
+
     def copies_for(self, one_copy: int) -> int:
         # Cache copies to rotate over: enough that a copy is evicted from the last-level cache before
         # it is read again (at least 2x its capacity between reuses), and at least four while they fit
@@ -136,6 +154,7 @@ class Bench:
 
         steps_prepared = [prepared(j, tuning) for j in range(copies)]
         steps, warmup = args.steps, args.warmup
+        self.ramp(steps_prepared)
         for i in range(warmup):
             steps_prepared[i % copies]()
         t.cuda.synchronize()
@@ -158,6 +177,7 @@ class Bench:
 
         # Single-launch latency (the metric's other half): launches each between their own pair of
         # events, so every launch starts on an idle stream.
+        self.ramp(steps_prepared, RAMP_MS / 2)
         n_lat = max(steps, min(200, int(0.3 / max(avg_ms * 1e-3, 1e-6))))
         starts = [t.cuda.Event(enable_timing=True) for _ in range(n_lat)]
         ends = [t.cuda.Event(enable_timing=True) for _ in range(n_lat)]
@@ -180,9 +200,7 @@ class Bench:
 
             def timed_schedule(tn):
                 calls = [prepared(j, tn) for j in range(copies)]
-                for i in range(3):
-                    calls[i % copies]()
-                t.cuda.synchronize()
+                self.ramp(calls, RAMP_MS / 2)
                 return self.back_to_back_ms(calls, reps, rounds=3)
 
             fs_tn, ns_tn = la.Tuning(fixed_split=-1), la.Tuning(fixed_split=1)
@@ -219,8 +237,11 @@ class Bench:
         extra = {}
         if full:
             extra = self.headline_extras(w, inp, ks, vs, steps_prepared, prepared, tuning, ws, one_copy, copies)
+        # The buffers go back to torch's allocator, NOT to the driver (no empty_cache()): the driver wipes
+        # device memory it gets back, in the background, and every kernel streams about 9 % slower for
+        # about 35 ms per GiB returned (measured: 7.2 -> 6.5 TB/s for 1.15 s after 32 GiB) -- which the
+        # next configuration's timed region would pay for.
         del ks, vs, steps_prepared, inp
-        t.cuda.empty_cache()
         return res, config, extra, w
 
     def span_balance(self, w, inp, ks, vs, out, ws, tuning, grid, copies):
@@ -265,9 +286,7 @@ class Bench:
         # the same K/V copy every step.
         warm_us = None
         if one_copy <= LLC_BYTES // 2:
-            for _ in range(10):
-                steps_prepared[0]()
-            t.cuda.synchronize()
+            self.ramp(steps_prepared[:1], RAMP_MS / 2)
             n_warm = 100
             wa = [t.cuda.Event(enable_timing=True) for _ in range(n_warm)]
             wb = [t.cuda.Event(enable_timing=True) for _ in range(n_warm)]
@@ -289,7 +308,7 @@ class Bench:
             captured = [prepared(j, tuning) for j in range(copies)]
             for i in range(n_graph):
                 captured[i % copies]()
-        for _ in range(2):
+        for _ in range(max(2, int(RAMP_MS / 2 * 1e-3 / max(one_copy / 6e12 * n_graph, 1e-6)))):
             graph.replay()
         t.cuda.synchronize()
         ga, gb = self.event_pair()
@@ -415,11 +434,9 @@ class Bench:
 
                 probes = [probe_call(j) for j in range(n_copies)]
                 reps = max(20, min(200, int(0.03 / (w.kv_bytes / 6e12))))
-                for i in range(2 * n_copies):
-                    calls[i % n_copies]()
-                    probes[i % n_copies]()
-                t.cuda.synchronize()
+                self.ramp(calls)
                 ms = self.back_to_back_ms(calls, reps, rounds=3)
+                self.ramp(probes, RAMP_MS / 2)
                 probe_ms = self.back_to_back_ms(probes, reps, rounds=3)
                 assert la.lean_attn_workspace_status(wsp) == 0
                 sweep.append({"B": B_s, "Hq": Hq_s, "Hkv": Hkv_s, "context": ctx, "kv_bytes": w.kv_bytes,
@@ -428,8 +445,7 @@ class Bench:
                               "frac": round(w.kv_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
                               "read_probe_us_per_step": round(probe_ms * 1e3, 2),
                               "over_probe_us": round((ms - probe_ms) * 1e3, 2)})
-                del inp, kv, calls, probes
-                t.cuda.empty_cache()
+                del inp, kv, calls, probes     # kept in torch's cache: see measure()
         return sweep
 
     # ---- LeanTile sweep (Section 4.2: the tile size is chosen per architecture by a sweep) -----------
@@ -504,8 +520,7 @@ class Bench:
                            "variants": rowset})
             print(f"tile sweep D={D} {dtype} rows={rows}: best shape {best['shape']} x{best['ctas_per_cu']} "
                   f"T_n={best['lean_tile']} {best['us']} us", file=sys.stderr, flush=True)
-            del inp, ks, vs, variants
-            t.cuda.empty_cache()
+            del inp, ks, vs, variants           # kept in torch's cache: see measure()
         return result
 
 
@@ -568,6 +583,7 @@ def main() -> int:
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "clock_ramp_ms": RAMP_MS,   # untimed sustained launches before the W warm-up steps of every timed region
         "ms_per_step": res["ms_per_step"],
         "latency_us": res["latency_us"],
         "launch_duration_us_avg": res["launch_duration_us_avg"],
