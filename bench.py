@@ -75,6 +75,7 @@ class Bench:
 
         self.torch, self.la, self.workloads, self.args = torch, la, workloads, args
         self.dev = torch.device("cuda:0")
+        self.ramp_ms = float(args.ramp_ms)
 
     # ---- helpers ------------------------------------------------------------------------------
     def event_pair(self):
@@ -95,12 +96,13 @@ class Bench:
             got.append(a.elapsed_time(b) / reps)
         return sorted(got)[len(got) // 2]
 
-    def ramp(self, calls, ms: float = RAMP_MS):
+    def ramp(self, calls, ms: float = None):
         """Keep the GPU busy with `calls` for `ms` milliseconds, untimed.  After an idle gap (input
         generation, a host-side pause) the first launches run 5-10 % slower until the clocks are back up
         (measured: about 15 ms of sustained load); every timed region starts after such a ramp so that it
         measures the steady state a decode loop runs in."""
         t = self.torch
+        ms = self.ramp_ms if ms is None else ms * self.ramp_ms / RAMP_MS
         t0 = time.perf_counter()
         i = 0
         while (time.perf_counter() - t0) * 1e3 < ms:
@@ -308,7 +310,7 @@ class Bench:
             captured = [prepared(j, tuning) for j in range(copies)]
             for i in range(n_graph):
                 captured[i % copies]()
-        for _ in range(max(2, int(RAMP_MS / 2 * 1e-3 / max(one_copy / 6e12 * n_graph, 1e-6)))):
+        for _ in range(max(2, int(self.ramp_ms / 2 * 1e-3 / max(one_copy / 6e12 * n_graph, 1e-6)))):
             graph.replay()
         t.cuda.synchronize()
         ga, gb = self.event_pair()
@@ -535,6 +537,9 @@ def main() -> int:
     ap.add_argument("--ctas-per-cu", type=int, default=0)
     ap.add_argument("--grid", type=int, default=0)
     ap.add_argument("--tile-shape", type=int, default=0, help="compiled LeanTile shape 1..9 (0: the library default for the shape of the problem)")
+    ap.add_argument("--ramp-ms", type=float, default=RAMP_MS,
+                    help="untimed sustained launches before every timed region (0 for profiler counter runs, "
+                         "where every launch is serialised and the clocks do not matter)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-schedule-comparison", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -583,7 +588,7 @@ def main() -> int:
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "clock_ramp_ms": RAMP_MS,   # untimed sustained launches before the W warm-up steps of every timed region
+        "clock_ramp_ms": args.ramp_ms,   # untimed sustained launches before the W warm-up steps of every timed region
         "ms_per_step": res["ms_per_step"],
         "latency_us": res["latency_us"],
         "launch_duration_us_avg": res["launch_duration_us_avg"],
