@@ -112,6 +112,34 @@ class Bench:
             t.cuda.synchronize()
         return i
 
+    def settle(self, quiet_s: float = 3.0, limit_s: float = 15.0):
+        """Wait until the device streams at its steady rate: memory that an earlier process returned to
+        the driver is wiped in the background (about 35 ms per GiB, so seconds after a large process) and
+        slows every kernel by about 9 % meanwhile -- at a rate that is steady in itself.  Reads 1 GiB
+        with the library's probe in windows of about 30 ms and returns once three windows in a row agree
+        within 1.5 % and either the rate has stepped up by more than 4 % since the start (the wipe ended)
+        or `quiet_s` seconds have passed without such a step (there was none; covers about 80 GiB).
+        Returns (milliseconds waited, GB/s of the last window, GB/s of the first)."""
+        t, la = self.torch, self.la
+        buf = t.empty(1 << 30, dtype=t.uint8, device=self.dev)
+        buf.fill_(1)
+        sink = t.zeros(64, dtype=t.int32, device=self.dev)
+        t0 = time.perf_counter()
+        rates = []
+        while time.perf_counter() - t0 < limit_s:
+            a, b = self.event_pair()
+            a.record()
+            for _ in range(200):
+                la.lean_attn_read_probe(buf, sink, 256, 2)
+            b.record()
+            t.cuda.synchronize()
+            rates.append(200 * buf.numel() / (a.elapsed_time(b) * 1e-3) / 1e9)
+            steady = len(rates) >= 4 and max(rates[-3:]) <= 1.015 * min(rates[-3:])
+            stepped_up = len(rates) >= 4 and min(rates[-3:]) > 1.04 * min(rates[1:-2])   # rates[0]: clock ramp
+            if steady and (stepped_up or time.perf_counter() - t0 >= quiet_s):
+                break
+        return round((time.perf_counter() - t0) * 1e3, 1), round(rates[-1], 1), round(rates[min(1, len(rates) - 1)], 1)
+
     def copies_for(self, one_copy: int) -> int:
         # Cache copies to rotate over: enough that a copy is evicted from the last-level cache before
         # it is read again (at least 2x its capacity between reuses), and at least four while they fit
@@ -564,6 +592,7 @@ def main() -> int:
     torch.cuda.set_device(0)
     props = torch.cuda.get_device_properties(0)
     bench = Bench(args)
+    settle_ms, settle_rate, settle_first = bench.settle() if args.ramp_ms > 0 else (0.0, None, None)
 
     per_config = []
     if args.workload == 0:
@@ -588,7 +617,10 @@ def main() -> int:
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "clock_ramp_ms": args.ramp_ms,   # untimed sustained launches before the W warm-up steps of every timed region
+        "clock_ramp_ms": args.ramp_ms,
+        "settle": {"waited_ms": settle_ms, "read_probe_GBps": settle_rate, "read_probe_GBps_at_start": settle_first,
+                   "note": "before the first configuration: read probe over 1 GiB until the rate is steady (memory freed "
+                           "by an earlier process is wiped in the background and slows all traffic meanwhile)"},   # untimed sustained launches before the W warm-up steps of every timed region
         "ms_per_step": res["ms_per_step"],
         "latency_us": res["latency_us"],
         "launch_duration_us_avg": res["launch_duration_us_avg"],
