@@ -92,6 +92,149 @@ struct Piece<2> {
     using type = u32x2;
 };
 
+// The arithmetic of one wave on its NBLK blocks of 16 tokens, common to the register-staged core
+// below and the LDS-staged core (lean_gqa_lds_core.h): the query operands, the running softmax
+// statistics and the output accumulators of MB blocks of 16 query rows.
+template <int DT, int D, int NBLK, int MB>
+struct GqaWave {
+    static constexpr int kKC = D / 32;   // 16-byte K pieces per lane per block
+    static constexpr int kEV = D / 16;   // head-dim elements per lane per token (V side)
+    u32x4 qb[MB][kKC];  // Q^T as B operands: lane (row r, g) holds Q[r][32*c2 + 8*g .. +8), zero rows past the block
+    int n_vis[MB];      // cached tokens the lane's query row may attend to (causal mask aligned to the end)
+    float m_run[MB];    // row 16*mb + r, shared by the four k-group lanes
+    float l_run[MB];    // this lane's share of l (tokens 4*i + g); summed over g at the end
+    f32x4 acc[MB][kEV];
+
+    __device__ __forceinline__ void load_q(const DecodeArgs& a, const TileRows& tr, int n_ctx, int r, int g) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+            for (int c2 = 0; c2 < kKC; ++c2) qb[mb][c2] = u32x4{0u, 0u, 0u, 0u};
+            n_vis[mb] = n_ctx;
+            if (16 * mb + r < tr.count) {
+                int token;
+                const int64_t qrow = query_row(a, tr, tr.rho0 + 16 * mb + r, &token);
+                if (a.causal) n_vis[mb] = n_ctx - tr.q_len + token + 1;
+                const u32x4* qp = reinterpret_cast<const u32x4*>(a.q + qrow * D) + g;
+#pragma unroll
+                for (int c2 = 0; c2 < kKC; ++c2) qb[mb][c2] = qp[4 * c2];
+            }
+            m_run[mb] = -INFINITY;
+            l_run[mb] = 0.f;
+#pragma unroll
+            for (int e = 0; e < kEV; ++e) acc[mb][e] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+
+    // One step: the K operands against Q, the online softmax, then O^T += V^T P^T.
+    // `base`: index in the context of the wave's first token of the step.  v(blk, j, i): dword i
+    // (head-dim elements 2i, 2i+1 of the lane's kEV) of token 4*j + g of block blk; the 4-token x kEV
+    // sub-block of a lane is transposed here into A operands.  between(): called once the scores are
+    // taken, before V is used.
+    template <class V, class F>
+    __device__ __forceinline__ void step(const u32x4 (&kb)[NBLK][kKC], int base, int g, float scale_log2e, V&& v, F&& between) {
+        uint2 p_hi[MB][NBLK], p_lo[MB][NBLK];  // P = P_hi + P_lo, two 16-bit parts
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            f32x4 s[NBLK];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int blk = 0; blk < NBLK; ++blk) {
+                // two accumulators halve the dependent MFMA chain over the head dim
+                f32x4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int c2 = 0; c2 < kKC; c2 += 2) {
+                    c0 = mfma32<DT>(kb[blk][c2], qb[mb][c2], c0);
+                    c1 = mfma32<DT>(kb[blk][c2 + 1], qb[mb][c2 + 1], c1);
+                }
+                f32x4 c = c0 + c1;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float x = c[i] * scale_log2e;
+                    if (base + blk * 16 + 4 * i + g >= n_vis[mb]) x = -INFINITY;  // tail and masked tokens
+                    c[i] = x;
+                    mx = fmaxf(mx, x);
+                }
+                s[blk] = c;
+            }
+            // The reference maximum m_run of a row is shared by its four k-group lanes.  It is
+            // only raised when some score of the wave exceeds it by more than kSlack (base-2
+            // units): any reference gives the same O~/l, so between updates P may reach 2^kSlack
+            // and the cross-lane maximum and the re-scaling of O stay off the common path.
+            constexpr float kSlack = 8.f;
+            float alpha = 1.f;
+            if (__any(mx > m_run[mb] + kSlack)) {
+                mx = fmaxf(mx, xor_shuffle(mx, 16));
+                mx = fmaxf(mx, xor_shuffle(mx, 32));
+                const float m_new = fmaxf(m_run[mb], mx);
+                const float m_new_ref = m_new == -INFINITY ? 0.f : m_new;
+                alpha = fast_exp2(m_run[mb] - m_new_ref);
+                m_run[mb] = m_new;
+            }
+            const float m_ref = m_run[mb] == -INFINITY ? 0.f : m_run[mb];
+            float psum = 0.f;
+#pragma unroll
+            for (int blk = 0; blk < NBLK; ++blk) {
+                float p[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    p[i] = fast_exp2(s[blk][i] - m_ref);
+                    psum += p[i];
+                }
+                split_pair<DT>(p[0], p[1], p_hi[mb][blk].x, p_lo[mb][blk].x);
+                split_pair<DT>(p[2], p[3], p_hi[mb][blk].y, p_lo[mb][blk].y);
+            }
+            l_run[mb] = l_run[mb] * alpha + psum;
+            if (__any(alpha != 1.f)) {  // the running max moved for some row of this wave
+#pragma unroll
+                for (int e = 0; e < kEV; ++e) acc[mb][e] *= alpha;
+            }
+        }
+        between();
+#pragma unroll
+        for (int blk = 0; blk < NBLK; ++blk) {
+#pragma unroll
+            for (int e = 0; e < kEV; ++e) {
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                // contraction slots 0..3: the four tokens against P_hi, 4..7: the same tokens against P_lo
+                const uint32_t v01 = __builtin_amdgcn_perm(v(blk, 1, e >> 1), v(blk, 0, e >> 1), sel);
+                const uint32_t v23 = __builtin_amdgcn_perm(v(blk, 3, e >> 1), v(blk, 2, e >> 1), sel);
+                const u32x4 va = {v01, v23, v01, v23};
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const u32x4 pb = {p_hi[mb][blk].x, p_hi[mb][blk].y, p_lo[mb][blk].x, p_lo[mb][blk].y};
+                    acc[mb][e] = mfma32<DT>(va, pb, acc[mb][e]);
+                }
+            }
+        }
+    }
+
+    // Segment end: the wave's partial (O~ rows, m, l) into its LDS area.  COL(m, e): head-dim index of
+    // element e of the lane with row index m.
+    template <class Smem, class COL>
+    __device__ __forceinline__ void park(Smem& sm, int w, int r, int g, COL&& col_of) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            // l over the four k-group lanes of each row; m is already common to them.
+            l_run[mb] += xor_shuffle(l_run[mb], 16);
+            l_run[mb] += xor_shuffle(l_run[mb], 32);
+            // 16-byte stores; rows are padded by 4 floats so that the 16 rows hit different banks
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int e4 = 0; e4 < kEV; e4 += 4) {
+                    const f32x4 val = {acc[mb][e4][i], acc[mb][e4 + 1][i], acc[mb][e4 + 2][i], acc[mb][e4 + 3][i]};
+                    *reinterpret_cast<f32x4*>(&sm.area[w].o[16 * mb + r][col_of(4 * g + i, e4)]) = val;
+                }
+            }
+            if (g == 0) {
+                sm.m[w][16 * mb + r] = m_run[mb];
+                sm.l[w][16 * mb + r] = l_run[mb];
+            }
+        }
+    }
+};
+
 // MB: blocks of 16 query rows that share one pass over K/V (T_m <= 16 * MB).  Every K and V
 // register tile feeds MB score and MB output contractions.
 template <int DT, int D, int NBLK, int NW, bool DB = true, int MB = 1>
@@ -162,31 +305,8 @@ struct GqaCore {
         const uint32_t stage_wr = (uint32_t)g * kStageRow + (uint32_t)r * (kPW * 4u);   // + (blk*16 + 4*j) rows
         const uint32_t stage_rd = (uint32_t)k_tok * kStageRow + (uint32_t)g * 16u;      // + blk*16 rows + 64*c2
 
-        // Q^T as B operands: lane (row r, g) holds Q[r][32*c2 + 8*g .. +8), zero rows past the block.
-        // n_vis: cached tokens the lane's query row may attend to (causal mask aligned to the end).
-        u32x4 qb[MB][kKC];
-        int n_vis[MB];
-        float m_run[MB];  // row 16*mb + r, shared by the four k-group lanes
-        float l_run[MB];  // this lane's share of l (tokens 4*i + g); summed over g at the end
-        f32x4 acc[MB][kEV];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-#pragma unroll
-            for (int c2 = 0; c2 < kKC; ++c2) qb[mb][c2] = u32x4{0u, 0u, 0u, 0u};
-            n_vis[mb] = n_ctx;
-            if (16 * mb + r < tr.count) {
-                int token;
-                const int64_t qrow = query_row(a, tr, tr.rho0 + 16 * mb + r, &token);
-                if (a.causal) n_vis[mb] = n_ctx - tr.q_len + token + 1;
-                const u32x4* qp = reinterpret_cast<const u32x4*>(a.q + qrow * D) + g;
-#pragma unroll
-                for (int c2 = 0; c2 < kKC; ++c2) qb[mb][c2] = qp[4 * c2];
-            }
-            m_run[mb] = -INFINITY;
-            l_run[mb] = 0.f;
-#pragma unroll
-            for (int e = 0; e < kEV; ++e) acc[mb][e] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
+        GqaWave<DT, D, NBLK, MB> wv;
+        wv.load_q(a, tr, n_ctx, r, g);
 
         vvec kA[NBLK][4], kB[NBLK][4];
         vvec vA[NBLK][4], vB[NBLK][4];
@@ -228,7 +348,6 @@ struct GqaCore {
 
         // The staged K tile against Q, the online softmax, then P against the V tile in registers.
         auto attend = [&](const vvec(&vb)[NBLK][4], int step) {
-            const int base = step * kTn + w * kCH;
             u32x4 kb[NBLK][kKC];
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk) {
@@ -237,79 +356,7 @@ struct GqaCore {
                     kb[blk][c2] = *reinterpret_cast<const u32x4*>(stage + stage_rd + (uint32_t)(blk * 16) * kStageRow + c2 * 64u);
             }
             __builtin_amdgcn_wave_barrier();
-            uint2 p_hi[MB][NBLK], p_lo[MB][NBLK];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                f32x4 s[NBLK];
-                float mx = -INFINITY;
-#pragma unroll
-                for (int blk = 0; blk < NBLK; ++blk) {
-                    // two accumulators halve the dependent MFMA chain over the head dim
-                    f32x4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int c2 = 0; c2 < kKC; c2 += 2) {
-                        c0 = mfma32<DT>(kb[blk][c2], qb[mb][c2], c0);
-                        c1 = mfma32<DT>(kb[blk][c2 + 1], qb[mb][c2 + 1], c1);
-                    }
-                    f32x4 c = c0 + c1;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        float x = c[i] * a.scale_log2e;
-                        if (base + blk * 16 + 4 * i + g >= n_vis[mb]) x = -INFINITY;  // tail and masked tokens
-                        c[i] = x;
-                        mx = fmaxf(mx, x);
-                    }
-                    s[blk] = c;
-                }
-                // The reference maximum m_run of a row is shared by its four k-group lanes.  It is
-                // only raised when some score of the wave exceeds it by more than kSlack (base-2
-                // units): any reference gives the same O~/l, so between updates P may reach 2^kSlack
-                // and the cross-lane maximum and the re-scaling of O stay off the common path.
-                constexpr float kSlack = 8.f;
-                float alpha = 1.f;
-                if (__any(mx > m_run[mb] + kSlack)) {
-                    mx = fmaxf(mx, xor_shuffle(mx, 16));
-                    mx = fmaxf(mx, xor_shuffle(mx, 32));
-                    const float m_new = fmaxf(m_run[mb], mx);
-                    const float m_new_ref = m_new == -INFINITY ? 0.f : m_new;
-                    alpha = fast_exp2(m_run[mb] - m_new_ref);
-                    m_run[mb] = m_new;
-                }
-                const float m_ref = m_run[mb] == -INFINITY ? 0.f : m_run[mb];
-                float psum = 0.f;
-#pragma unroll
-                for (int blk = 0; blk < NBLK; ++blk) {
-                    float p[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        p[i] = fast_exp2(s[blk][i] - m_ref);
-                        psum += p[i];
-                    }
-                    split_pair<DT>(p[0], p[1], p_hi[mb][blk].x, p_lo[mb][blk].x);
-                    split_pair<DT>(p[2], p[3], p_hi[mb][blk].y, p_lo[mb][blk].y);
-                }
-                l_run[mb] = l_run[mb] * alpha + psum;
-                if (__any(alpha != 1.f)) {  // the running max moved for some row of this wave
-#pragma unroll
-                    for (int e = 0; e < kEV; ++e) acc[mb][e] *= alpha;
-                }
-            }
-#pragma unroll
-            for (int blk = 0; blk < NBLK; ++blk) {
-#pragma unroll
-                for (int e = 0; e < kEV; ++e) {
-                    const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-                    // contraction slots 0..3: the four tokens against P_hi, 4..7: the same tokens against P_lo
-                    const uint32_t v01 = __builtin_amdgcn_perm(vb[blk][1].dword(e >> 1), vb[blk][0].dword(e >> 1), sel);
-                    const uint32_t v23 = __builtin_amdgcn_perm(vb[blk][3].dword(e >> 1), vb[blk][2].dword(e >> 1), sel);
-                    const u32x4 va = {v01, v23, v01, v23};
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
-                        const u32x4 pb = {p_hi[mb][blk].x, p_hi[mb][blk].y, p_lo[mb][blk].x, p_lo[mb][blk].y};
-                        acc[mb][e] = mfma32<DT>(va, pb, acc[mb][e]);
-                    }
-                }
-            }
+            wv.step(kb, step * kTn + w * kCH, g, a.scale_log2e, [&](int blk, int j, int i) { return vb[blk][j].dword(i); }, [] {});
         };
 
         // The LeanTile iterations of the segment are visited in ascending order by every CTA.
@@ -369,25 +416,7 @@ struct GqaCore {
             }
         }
 
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            // l over the four k-group lanes of each row; m is already common to them.
-            l_run[mb] += xor_shuffle(l_run[mb], 16);
-            l_run[mb] += xor_shuffle(l_run[mb], 32);
-            // 16-byte stores; rows are padded by 4 floats so that the 16 rows hit different banks
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-#pragma unroll
-                for (int e4 = 0; e4 < kEV; e4 += 4) {
-                    const f32x4 v = {acc[mb][e4][i], acc[mb][e4 + 1][i], acc[mb][e4 + 2][i], acc[mb][e4 + 3][i]};
-                    *reinterpret_cast<f32x4*>(&sm.area[w].o[16 * mb + r][col_of(4 * g + i, e4)]) = v;
-                }
-            }
-            if (g == 0) {
-                sm.m[w][16 * mb + r] = m_run[mb];
-                sm.l[w][16 * mb + r] = l_run[mb];
-            }
-        }
+        wv.park(sm, w, r, g, [](int m, int e) { return col_of(m, e); });
         __syncthreads();
     }
 };

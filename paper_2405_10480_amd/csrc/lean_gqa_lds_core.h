@@ -110,31 +110,8 @@ struct GqaLdsCore {
             k_rd[c2] = (uint32_t)k_tok * kRowBytes + (((uint32_t)(4 * c2 + g) ^ (uint32_t)k_tok) * 16u);
         Stage* const stages = sm.area[w].st;
 
-        // Q^T as B operands: lane (row r, g) holds Q[r][32*c2 + 8*g .. +8), zero rows past the block.
-        // n_vis: cached tokens the lane's query row may attend to (causal mask aligned to the end).
-        u32x4 qb[MB][kKC];
-        int n_vis[MB];
-        float m_run[MB];  // row 16*mb + r, shared by the four k-group lanes
-        float l_run[MB];  // this lane's share of l (tokens 4*i + g); summed over g at the end
-        f32x4 acc[MB][kEV];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-#pragma unroll
-            for (int c2 = 0; c2 < kKC; ++c2) qb[mb][c2] = u32x4{0u, 0u, 0u, 0u};
-            n_vis[mb] = n_ctx;
-            if (16 * mb + r < tr.count) {
-                int token;
-                const int64_t qrow = query_row(a, tr, tr.rho0 + 16 * mb + r, &token);
-                if (a.causal) n_vis[mb] = n_ctx - tr.q_len + token + 1;
-                const u32x4* qp = reinterpret_cast<const u32x4*>(a.q + qrow * D) + g;
-#pragma unroll
-                for (int c2 = 0; c2 < kKC; ++c2) qb[mb][c2] = qp[4 * c2];
-            }
-            m_run[mb] = -INFINITY;
-            l_run[mb] = 0.f;
-#pragma unroll
-            for (int e = 0; e < kEV; ++e) acc[mb][e] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
+        GqaWave<DT, D, NBLK, MB> wv;
+        wv.load_q(a, tr, n_ctx, r, g);
 
         // Fill one stage: `off` is the byte offset of the wave's tile in the slab (an offset past
         // the slab writes zeros to LDS without any memory traffic).
@@ -160,7 +137,6 @@ struct GqaLdsCore {
         // One staged K tile against Q, the online softmax, then P against the staged V tile.
         auto attend = [&](auto stage_index, int step) {
             constexpr int s = decltype(stage_index)::value;
-            const int base = step * kTn + w * kCH;
             const char* kbuf = reinterpret_cast<const char*>(stages[s].k);
             u32x4 kb[NBLK][kKC];
 #pragma unroll
@@ -178,79 +154,8 @@ struct GqaLdsCore {
                     for (int p = 0; p < kPieces; ++p) vb[blk][j][p] = stages[s].v[((blk * 4 + j) * kPieces + p) * 64 + lane];
                 }
             }
-            uint2 p_hi[MB][NBLK], p_lo[MB][NBLK];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                f32x4 sc[NBLK];
-                float mx = -INFINITY;
-#pragma unroll
-                for (int blk = 0; blk < NBLK; ++blk) {
-                    // two accumulators halve the dependent MFMA chain over the head dim
-                    f32x4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int c2 = 0; c2 < kKC; c2 += 2) {
-                        c0 = mfma32<DT>(kb[blk][c2], qb[mb][c2], c0);
-                        c1 = mfma32<DT>(kb[blk][c2 + 1], qb[mb][c2 + 1], c1);
-                    }
-                    f32x4 c = c0 + c1;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        float x = c[i] * a.scale_log2e;
-                        if (base + blk * 16 + 4 * i + g >= n_vis[mb]) x = -INFINITY;  // tail and masked tokens
-                        c[i] = x;
-                        mx = fmaxf(mx, x);
-                    }
-                    sc[blk] = c;
-                }
-                // The reference maximum of a row only moves when a score exceeds it by more than
-                // kSlack (base-2 units): any reference gives the same O~/l (see GqaCore).
-                constexpr float kSlack = 8.f;
-                float alpha = 1.f;
-                if (__any(mx > m_run[mb] + kSlack)) {
-                    mx = fmaxf(mx, xor_shuffle(mx, 16));
-                    mx = fmaxf(mx, xor_shuffle(mx, 32));
-                    const float m_new = fmaxf(m_run[mb], mx);
-                    const float m_new_ref = m_new == -INFINITY ? 0.f : m_new;
-                    alpha = fast_exp2(m_run[mb] - m_new_ref);
-                    m_run[mb] = m_new;
-                }
-                const float m_ref = m_run[mb] == -INFINITY ? 0.f : m_run[mb];
-                float psum = 0.f;
-#pragma unroll
-                for (int blk = 0; blk < NBLK; ++blk) {
-                    float p[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        p[i] = fast_exp2(sc[blk][i] - m_ref);
-                        psum += p[i];
-                    }
-                    split_pair<DT>(p[0], p[1], p_hi[mb][blk].x, p_lo[mb][blk].x);
-                    split_pair<DT>(p[2], p[3], p_hi[mb][blk].y, p_lo[mb][blk].y);
-                }
-                l_run[mb] = l_run[mb] * alpha + psum;
-                if (__any(alpha != 1.f)) {  // the running max moved for some row of this wave
-#pragma unroll
-                    for (int e = 0; e < kEV; ++e) acc[mb][e] *= alpha;
-                }
-            }
-            wait_lds_reads();   // the stage may be refilled from here on
-#pragma unroll
-            for (int blk = 0; blk < NBLK; ++blk) {
-#pragma unroll
-                for (int e = 0; e < kEV; ++e) {
-                    const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-                    const int p = e / kPE, d = (e % kPE) >> 1;
-                    // contraction slots 0..3: the four tokens against P_hi, 4..7: the same tokens against P_lo
-                    const uint32_t v01 = __builtin_amdgcn_perm(vb[blk][1][p][d], vb[blk][0][p][d], sel);
-                    const uint32_t v23 = __builtin_amdgcn_perm(vb[blk][3][p][d], vb[blk][2][p][d], sel);
-                    const u32x4 va = {v01, v23, v01, v23};
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
-                        const u32x4 pb = {p_hi[mb][blk].x, p_hi[mb][blk].y, p_lo[mb][blk].x, p_lo[mb][blk].y};
-                        acc[mb][e] = mfma32<DT>(va, pb, acc[mb][e]);
-                    }
-                }
-            }
+            wv.step(kb, step * kTn + w * kCH, g, a.scale_log2e, [&](int blk, int j, int i) { return vb[blk][j][i / 4][i % 4]; },
+                    [] { wait_lds_reads(); });   // the stage may be refilled once its reads have returned
         };
 
         const int it_first = sg.local_iter;
@@ -288,25 +193,7 @@ struct GqaLdsCore {
         // the loads still outstanding write (zeros) into the area the partial is parked in next
         wait_loads_outstanding<0>();
 
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            // l over the four k-group lanes of each row; m is already common to them.
-            l_run[mb] += xor_shuffle(l_run[mb], 16);
-            l_run[mb] += xor_shuffle(l_run[mb], 32);
-            // 16-byte stores; rows are padded by 4 floats so that the 16 rows hit different banks
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-#pragma unroll
-                for (int e4 = 0; e4 < kEV; e4 += 4) {
-                    const f32x4 v = {acc[mb][e4][i], acc[mb][e4 + 1][i], acc[mb][e4 + 2][i], acc[mb][e4 + 3][i]};
-                    *reinterpret_cast<f32x4*>(&sm.area[w].o[16 * mb + r][col_of(4 * g + i, e4)]) = v;
-                }
-            }
-            if (g == 0) {
-                sm.m[w][16 * mb + r] = m_run[mb];
-                sm.l[w][16 * mb + r] = l_run[mb];
-            }
-        }
+        wv.park(sm, w, r, g, [](int m, int e) { return col_of(m, e); });
         __syncthreads();
     }
 };
