@@ -348,6 +348,7 @@ struct GqaCore {
 
         // The staged K tile against Q, the online softmax, then P against the V tile in registers.
         auto attend = [&](const vvec(&vb)[NBLK][4], int step) {
+            const int base = step * kTn + w * kCH;
             u32x4 kb[NBLK][kKC];
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk) {
@@ -356,7 +357,7 @@ struct GqaCore {
                     kb[blk][c2] = *reinterpret_cast<const u32x4*>(stage + stage_rd + (uint32_t)(blk * 16) * kStageRow + c2 * 64u);
             }
             __builtin_amdgcn_wave_barrier();
-            wv.step(kb, step * kTn + w * kCH, g, a.scale_log2e, [&](int blk, int j, int i) { return vb[blk][j].dword(i); }, [] {});
+            wv.step(kb, base, g, a.scale_log2e, [&](int blk, int j, int i) { return vb[blk][j].dword(i); }, [] {});
         };
 
         // The LeanTile iterations of the segment are visited in ascending order by every CTA.
