@@ -92,7 +92,8 @@ typedef enum lean_attn_kv_layout { LEAN_ATTN_KV_PADDED = 0, LEAN_ATTN_KV_PACKED 
  * (the last may hold fewer).
  * Output tile = one (sequence, KV head, row block); it owns ceil(N_b / T_n)
  * LeanTile iterations.  CTA g owns iterations
- * [g*iters_per_cta + min(g, extra), ... + iters_per_cta + (g < extra)).
+ * [g*iters_per_cta + min(g, extra), ... + iters_per_cta + (g < extra))
+ * (see tail_grid for the optional short spans at the end of the line).
  * For decode with up to 32 query heads per KV head, C_m = 1 and T_m = Hq / Hkv.
  */
 typedef struct lean_attn_plan {
@@ -111,6 +112,11 @@ typedef struct lean_attn_plan {
     int32_t C_m;              /* row blocks per KV head */
     int32_t tile_shape;       /* the compiled tile shape used, 1..9 (lean_attn_tuning.tile_shape, or the library's
                                  default for this head dim, dtype and T_m) */
+    int32_t tail_grid;        /* P: the last P of the `grid` workgroups own short spans (0: none).  Then
+                                 iters_per_cta and extra describe the first G = grid - P workgroups, which share
+                                 the first total_iters - tail_iters iterations, and workgroup G + j owns
+                                 floor(tail_iters / P) (+ 1 for j < tail_iters mod P) of the last tail_iters */
+    int64_t tail_iters;
 } lean_attn_plan;
 
 /*
@@ -123,7 +129,10 @@ typedef struct lean_attn_tuning {
     int32_t ctas_per_cu;   /* workgroups per compute unit used to size the default G */
     int32_t num_cus;       /* pretend the device has this many compute units (schedule queries) */
     int32_t kernel;        /* 0 default, 1 force VALU kernel (needs N_q * Hq == Hkv), 2 force MFMA kernel */
-    int32_t reserved_;     /* must be 0 */
+    int32_t tail_grid;     /* 0: none.  P > 0: the last share of the iteration line is cut into P short spans for P
+                              further workgroups (grid = G + P), which the hardware starts as the first G retire:
+                              a static decomposition that still lets the faster units take more of the tail.
+                              Ignored when the problem is too small; not with fixed_split or lean_attn_attend_prepare */
     int32_t spin_limit;    /* polls before a waiting CTA gives up and reports PEER_TIMEOUT */
     int32_t merge_fanin;   /* 0 default: every CTA of a shared tile publishes its partial and the tile's last
                               1..8 CTAs each merge one slice of all partials and write it (one level).
@@ -145,7 +154,7 @@ typedef struct lean_attn_tuning {
     int32_t debug_delay_signal; /* ... and this many between the acknowledged stores and the flag store
                                    (widens the window between StorePartials and Signal of Algorithm 2) */
     int32_t debug_delay_stride; /* only workgroups with id % stride == stride - 1 sleep (0 or 1: all of them) */
-    int32_t reserved2_;         /* must be 0 */
+    int32_t tail_permille;      /* share of the iterations the tail spans cover, in 1/1000 (0: library default, max 500) */
     void* cta_clock;       /* device, 16 uint64 per CTA of the grid, or NULL: 100 MHz timestamps
                               [0] kernel entry, [1] end of the span loop, [2] first segment located, [3] exit,
                               [7] first LeanTile iteration done, [8] first segment streamed, [9] partial stores

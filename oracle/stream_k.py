@@ -34,11 +34,20 @@ import numpy as np
 from . import rescale
 
 
-def span_edges(total_iters: int, G: int) -> np.ndarray:
-    """Cut points of the spans: workgroup g owns iterations [edges[g], edges[g+1])."""
+def span_edges(total_iters: int, G: int, tail=None) -> np.ndarray:
+    """Cut points of the spans: workgroup g owns iterations [edges[g], edges[g+1]).
+
+    ``tail = (P, tail_iters)``: the last ``tail_iters`` iterations are cut into ``P`` near-equal spans of
+    their own (workgroups G .. G+P-1) and the first ``G`` workgroups share the rest: the decomposition
+    is still a set of consecutive intervals, which is all Section 4.3 needs."""
     if total_iters <= 0:
         return np.zeros(1, dtype=np.int64)
     G = max(1, min(int(G), int(total_iters)))
+    if tail is not None and tail[0] > 0:
+        P, tail_iters = int(tail[0]), int(tail[1])
+        assert P <= tail_iters <= total_iters - G
+        head = span_edges(total_iters - tail_iters, G)
+        return np.concatenate([head, head[-1] + span_edges(tail_iters, P)[1:]])
     g = np.arange(G + 1, dtype=np.int64)
     return g * (total_iters // G) + np.minimum(g, total_iters % G)
 
@@ -62,14 +71,14 @@ def tile_edges(seqlens, Hkv: int, T_n: int, order: str = "padded"):
     return tiles, np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
 
 
-def pieces(seqlens, Hkv: int, T_n: int, G: int, order: str = "padded"):
+def pieces(seqlens, Hkv: int, T_n: int, G: int, order: str = "padded", tail=None):
     """Every (workgroup, output tile) overlap, in iteration order.
 
     One dict per piece: cta, tile, b, h, local_iter, local_iter_end (iterations within the tile),
     host (the piece holds the tile's first iteration), finishing (it holds the last),
     first_cta / last_cta (the workgroups of the tile's first and last piece)."""
     tiles, t_edges = tile_edges(seqlens, Hkv, T_n, order)
-    s_edges = span_edges(int(t_edges[-1]), G)
+    s_edges = span_edges(int(t_edges[-1]), G, tail)
     cuts = np.union1d(t_edges, s_edges)
     out = []
     for lo, hi in zip(cuts[:-1], cuts[1:]):

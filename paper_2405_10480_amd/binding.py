@@ -31,7 +31,7 @@ class Plan(ctypes.Structure):
         ("grid", ctypes.c_int32), ("total_iters", ctypes.c_int64), ("iters_per_cta", ctypes.c_int64),
         ("extra", ctypes.c_int32), ("block_threads", ctypes.c_int32), ("max_resident", ctypes.c_int32),
         ("kernel", ctypes.c_int32), ("fixed_split", ctypes.c_int32), ("C_m", ctypes.c_int32),
-        ("tile_shape", ctypes.c_int32),
+        ("tile_shape", ctypes.c_int32), ("tail_grid", ctypes.c_int32), ("tail_iters", ctypes.c_int64),
     ]
 
 
@@ -62,10 +62,10 @@ class Problem(ctypes.Structure):
 class Tuning(ctypes.Structure):
     _fields_ = [
         ("grid", ctypes.c_int32), ("ctas_per_cu", ctypes.c_int32), ("num_cus", ctypes.c_int32),
-        ("kernel", ctypes.c_int32), ("reserved_", ctypes.c_int32), ("spin_limit", ctypes.c_int32),
+        ("kernel", ctypes.c_int32), ("tail_grid", ctypes.c_int32), ("spin_limit", ctypes.c_int32),
         ("merge_fanin", ctypes.c_int32), ("tile_shape", ctypes.c_int32), ("grid_multiple", ctypes.c_int32), ("fixed_split", ctypes.c_int32),
         ("debug_delay_store", ctypes.c_int32), ("debug_delay_signal", ctypes.c_int32),
-        ("debug_delay_stride", ctypes.c_int32), ("reserved2_", ctypes.c_int32),
+        ("debug_delay_stride", ctypes.c_int32), ("tail_permille", ctypes.c_int32),
         ("cta_clock", ctypes.c_void_p),
     ]
 

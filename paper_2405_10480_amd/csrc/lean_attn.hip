@@ -21,6 +21,7 @@ static_assert(kMaxGrid == LEAN_ATTN_MAX_GRID, "header and workspace layout disag
 // Defaults picked by the LeanTile sweep on MI355X (the paper fixes the tile size per architecture
 // after an empirical sweep, Section 4.2).
 constexpr int kDefaultCtasPerCu = 1;
+constexpr int kDefaultTailPermille = 60;  // share of the iterations the tail spans cover when asked for without one
 constexpr int kShortContextTokens = 1536;  // mean context at or below which two workgroups share a unit
 constexpr int kDefaultGridMultiple = 1;
 constexpr int kMaxProbeMode = 6;
@@ -175,7 +176,7 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
     lean_attn_tuning t;
     std::memset(&t, 0, sizeof t);
     if (tn) t = *tn;
-    if (t.grid < 0 || t.ctas_per_cu < 0 || t.num_cus < 0 || t.kernel < 0 || t.kernel > 2 || t.reserved_ != 0 ||
+    if (t.grid < 0 || t.ctas_per_cu < 0 || t.num_cus < 0 || t.kernel < 0 || t.kernel > 2 || t.tail_grid < 0 || t.tail_permille < 0 || t.tail_permille > 500 ||
         t.debug_delay_store < 0 || t.debug_delay_store > 64 ||
         t.debug_delay_signal < 0 || t.debug_delay_signal > 64 || t.debug_delay_stride < 0 || t.spin_limit < 0 || t.merge_fanin < 0 || t.merge_fanin == 1 || t.tile_shape < 0 ||
         t.tile_shape > kNumShapes || t.grid_multiple < 0 || t.fixed_split < -1)
@@ -266,13 +267,29 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
         if (G > 65535 || (split > 1 && G > LEAN_ATTN_MAX_GRID)) return LEAN_ATTN_ERR_TUNING;
     }
 
+    // Tail spans: the last share of the line in short spans for `tail_grid` further workgroups, which
+    // the hardware dispatches as the first G retire.  Not for the baseline schedules, and dropped when
+    // the problem is too small to leave every one of the first G workgroups an iteration.
+    int64_t P = 0, tail_iters = 0;
+    if (split == 0 && t.tail_grid > 0) {
+        if (full_grid || G + t.tail_grid > LEAN_ATTN_MAX_GRID) return LEAN_ATTN_ERR_TUNING;
+        P = t.tail_grid;
+        tail_iters = I * (t.tail_permille > 0 ? t.tail_permille : kDefaultTailPermille) / 1000;
+        if (tail_iters < P) tail_iters = P;
+        if (I - tail_iters < G) P = tail_iters = 0;
+    }
+    Sched spans;
+    set_spans(spans, I, (int32_t)(G + P), (int32_t)P, tail_iters);
+
     plan->T_n = T_n;
     plan->T_m = T_m;
     plan->num_output_tiles = B * heads;
-    plan->grid = (int32_t)G;
+    plan->grid = spans.grid;
     plan->total_iters = I;
-    plan->iters_per_cta = I / G;
-    plan->extra = (int32_t)(I % G);
+    plan->iters_per_cta = spans.iters_per_cta;
+    plan->extra = spans.extra;
+    plan->tail_grid = spans.tail_grid;
+    plan->tail_iters = tail_iters;
     plan->block_threads = var.threads;
     plan->max_resident = (int32_t)resident;
     plan->kernel = kernel;
@@ -284,10 +301,7 @@ static int make_schedule(const lean_attn_problem& p, const int32_t* seqlens, con
         sched->Hkv = heads;
         sched->T_n = T_n;
         sched->packed = kv_layout == LEAN_ATTN_KV_PACKED;
-        sched->grid = plan->grid;
-        sched->extra = plan->extra;
-        sched->total_iters = I;
-        sched->iters_per_cta = plan->iters_per_cta;
+        set_spans(*sched, I, spans.grid, spans.tail_grid, tail_iters);
         sched->fixed_split = split;
         if (table) finish_sched(*sched, *table);
     }
@@ -383,10 +397,10 @@ int lean_attn_walk(const lean_attn_plan* plan, const int32_t* seqlens, int B, in
     s.Hkv = heads;
     s.T_n = plan->T_n;
     s.packed = kv_layout == LEAN_ATTN_KV_PACKED;
-    s.grid = plan->grid;
-    s.extra = plan->extra;
-    s.total_iters = plan->total_iters;
-    s.iters_per_cta = plan->iters_per_cta;
+    if (plan->tail_grid < 0 || plan->tail_grid >= plan->grid || plan->tail_iters < 0 || plan->tail_iters > plan->total_iters)
+        return LEAN_ATTN_ERR_BAD_SHAPE;
+    set_spans(s, plan->total_iters, plan->grid, plan->tail_grid, plan->tail_iters);
+    if (s.extra != plan->extra || s.iters_per_cta != plan->iters_per_cta) return LEAN_ATTN_ERR_BAD_SHAPE;
     s.fixed_split = plan->fixed_split;
     finish_sched(s, t);
     if (iters * heads != plan->total_iters) return LEAN_ATTN_ERR_BAD_SHAPE;
@@ -618,7 +632,7 @@ int lean_attn_attend_prepare(const lean_attn_problem* problem, const void* q, co
     if ((((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out | (uintptr_t)block_host) & 15) != 0)
         return LEAN_ATTN_ERR_BAD_SHAPE;
     if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < kPartialsOffset) return LEAN_ATTN_ERR_WORKSPACE;
-    if (tuning && (tuning->fixed_split != 0 || tuning->tile_shape != 0)) return LEAN_ATTN_ERR_TUNING;
+    if (tuning && (tuning->fixed_split != 0 || tuning->tile_shape != 0 || tuning->tail_grid != 0)) return LEAN_ATTN_ERR_TUNING;
     int64_t tok_total = 0;
     rc = check_lengths(p, seqlens, &tok_total);
     if (rc != LEAN_ATTN_OK) return rc;

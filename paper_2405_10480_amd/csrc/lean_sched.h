@@ -13,6 +13,11 @@
 //                depend on the order, each follows its layout in memory).
 // Spans:         CTA g owns [g*q + min(g, r), +q + (g < r)) with q = I / G, r = I mod G
 //                (the paper divides I by G and is silent on a remainder).
+// Tail spans:    optionally the last `tail_iters` iterations of the line are cut into `tail_grid`
+//                short spans of their own, owned by the workgroups after the first G: equal shares
+//                do not finish at the same time (the units do not stream equally fast), and the
+//                hardware hands the short spans, in order, to whichever units finish first.  The
+//                decomposition stays a fixed function of the problem, so results stay reproducible.
 // Fixed split:   the schedule LeanAttention is compared against (Section 3.3) and one of
 //                its special cases (Section 4.3): every output tile is cut into `split`
 //                near-equal parts, CTA g = tile_idx*split + part, G = tiles*split; split = 1
@@ -70,10 +75,10 @@ struct Sched {
     int32_t Hkv;            // output tiles per sequence: KV heads x row blocks per KV head (C_m)
     int32_t T_n;
     int32_t packed;         // 0: PADDED order b->h->t, 1: PACKED order h->b->t
-    int32_t grid;           // G
-    int32_t extra;          // I mod G
+    int32_t grid;           // workgroups: the first head_grid with long spans, then tail_grid with short ones
+    int32_t extra;          // head_iters mod head_grid
     int64_t total_iters;    // I
-    int64_t iters_per_cta;  // I / G
+    int64_t iters_per_cta;  // head_iters / head_grid
     int32_t fixed_split;    // 0: stream-K spans; s >= 1: fixed split into s parts per output tile
     int32_t uniform_cn;     // > 0: every sequence owns this many LeanTile iterations (no table search)
     // multipliers for the divisors of the walk; valid (and used) only while I < 2^31 - 1
@@ -82,7 +87,29 @@ struct Sched {
     Magic by_heads;         // Hkv (PADDED order: iteration -> sequence key)
     Magic by_per_head;      // cuC[B] (PACKED order: iteration -> head)
     Magic by_cn;            // uniform_cn
+    // tail spans (tail_grid == 0: none; then head_grid == grid and head_iters == total_iters)
+    int32_t head_grid;      // G
+    int32_t tail_grid;      // workgroups with short spans
+    int64_t head_iters;     // iterations [0, head_iters) belong to the first head_grid workgroups
+    int32_t tail_ipc;       // (I - head_iters) / tail_grid
+    int32_t tail_extra;     // (I - head_iters) mod tail_grid
+    Magic by_tipc;          // tail_ipc
+    Magic by_tipc1;         // tail_ipc + 1
 };
+
+// Sets the span fields of a schedule of `grid` workgroups, the last `tail_grid` of which share the
+// last `tail_iters` iterations (0, 0: plain stream-K spans).  Needs grid - tail_grid >= 1.
+inline void set_spans(Sched& s, int64_t total_iters, int32_t grid, int32_t tail_grid, int64_t tail_iters) {
+    s.total_iters = total_iters;
+    s.grid = grid;
+    s.tail_grid = tail_grid;
+    s.head_grid = grid - tail_grid;
+    s.head_iters = total_iters - tail_iters;
+    s.iters_per_cta = s.head_iters / s.head_grid;
+    s.extra = (int32_t)(s.head_iters % s.head_grid);
+    s.tail_ipc = tail_grid > 0 ? (int32_t)(tail_iters / tail_grid) : 0;
+    s.tail_extra = tail_grid > 0 ? (int32_t)(tail_iters % tail_grid) : 0;
+}
 
 // One output-tile segment of a CTA's span (one trip of Algorithm 2's loop).
 struct Segment {
@@ -108,7 +135,7 @@ LEAN_HD int64_t div_iters(const Sched& s, int64_t a, int64_t b) {
 
 constexpr int64_t kMagicLimit = 0x7fffffff;  // iteration spaces below this divide by multiplication
 
-// Fills the derived fields of a schedule whose B, Hkv, grid, total_iters, iters_per_cta are set.
+// Fills the derived fields of a schedule whose B, Hkv and span fields (set_spans) are set.
 inline void finish_sched(Sched& s, const SchedTable& t) {
     s.uniform_cn = 0;
     if (s.B >= 1) {
@@ -123,10 +150,22 @@ inline void finish_sched(Sched& s, const SchedTable& t) {
     s.by_heads = make_magic(small ? (uint32_t)s.Hkv : 1u);
     s.by_per_head = make_magic(small && s.B >= 1 ? (uint32_t)t.cu_iters[s.B] : 1u);
     s.by_cn = make_magic(small && s.uniform_cn > 0 ? (uint32_t)s.uniform_cn : 1u);
+    s.by_tipc = make_magic(small && s.tail_ipc > 0 ? (uint32_t)s.tail_ipc : 1u);
+    s.by_tipc1 = make_magic(small ? (uint32_t)s.tail_ipc + 1u : 1u);
 }
 
 // The CTA whose span holds global iteration `it` (stream-K spans).
 LEAN_HD int cta_of_iter(const Sched& s, int64_t it) {
+    if (it >= s.head_iters) {  // a tail span (never taken without tail spans: it < total_iters)
+        const int64_t j = it - s.head_iters;
+        const int64_t fat_t = (int64_t)s.tail_extra * (s.tail_ipc + 1);
+        if (s.total_iters < kMagicLimit) {
+            if (j < fat_t) return s.head_grid + (int)magic_div((uint32_t)j, s.by_tipc1);
+            return s.head_grid + s.tail_extra + (int)magic_div((uint32_t)(j - fat_t), s.by_tipc);
+        }
+        if (j < fat_t) return s.head_grid + (int)(j / (s.tail_ipc + 1));
+        return s.head_grid + s.tail_extra + (int)((j - fat_t) / s.tail_ipc);
+    }
     const int64_t fat = (int64_t)s.extra * (s.iters_per_cta + 1);
     if (s.total_iters < kMagicLimit) {
         if (it < fat) return (int)magic_div((uint32_t)it, s.by_ipc1);
@@ -233,6 +272,13 @@ LEAN_HD Segment locate_next(const Sched& s, const SchedTable& t, const Segment& 
 // The range of global iterations CTA g owns (empty when begin == end).
 LEAN_HD void span_of(const Sched& s, const SchedTable& t, int g, int64_t* begin, int64_t* end) {
     if (!s.fixed_split) {
+        if (g >= s.head_grid) {  // a tail span
+            const int j = g - s.head_grid;
+            const int64_t lo = s.head_iters + (int64_t)j * s.tail_ipc + (j < s.tail_extra ? j : s.tail_extra);
+            *begin = lo;
+            *end = lo + s.tail_ipc + (j < s.tail_extra ? 1 : 0);
+            return;
+        }
         const int64_t lo = (int64_t)g * s.iters_per_cta + (g < s.extra ? g : s.extra);
         *begin = lo;
         *end = lo + s.iters_per_cta + (g < s.extra ? 1 : 0);

@@ -903,3 +903,25 @@ def test_one_captured_graph_serves_changing_lengths(group, N_q):
     want, _ = oracle.attention(q4, inp.k, inp.v, steps[-1], N_q=N_q, Hq=w0.Hq, Hkv=Hkv, D=D, scale=w0.scale,
                                causal=causal, n_stride=stride)
     _check(out.cpu().numpy(), None, want, None, "after a refused update")
+
+
+@pytest.mark.parametrize("group", [1, 4, 20])
+def test_tail_spans_against_the_oracle(group):
+    # tuning.tail_grid: the end of the iteration line in short spans for further workgroups, which start
+    # as the first ones retire -- another decomposition of the same sum (Section 4.1), both cores
+    Hkv, D = 2, 128
+    seqlens = [30011, 517, 0, 9000]
+    inp = _mk(4, Hkv * group, Hkv, D, "bf16", seqlens, workloads.KV_PACKED, seed=71 + group, outlier=0.01)
+    want, want_lse = _oracle(inp)
+    code = la.BF16
+    with_tail = 0
+    for tn in (la.Tuning(tail_grid=64), la.Tuning(tail_grid=256, tail_permille=200), la.Tuning(grid=7, tail_grid=3, tail_permille=500),
+               la.Tuning(grid=64, tail_grid=1000, tail_permille=1), la.Tuning(tail_grid=16, merge_fanin=3), la.Tuning(grid=700, tail_grid=300)):
+        plan = la.lean_attn_schedule(seqlens, Hkv * group, Hkv, D, code, la.KV_PACKED, tn)
+        assert plan.tail_grid in (0, tn.tail_grid) and plan.grid > plan.tail_grid     # 0: too few iterations for this tail
+        with_tail += plan.tail_grid > 0
+        got, got_lse, _ = _run(inp, tn)
+        _check(got, got_lse, want, want_lse, f"g{group} grid={plan.grid} tail={plan.tail_grid}/{plan.tail_iters}")
+        again, again_lse, _ = _run(inp, tn)
+        assert np.array_equal(got, again) and np.array_equal(got_lse, again_lse)      # a static decomposition
+    assert with_tail >= 4

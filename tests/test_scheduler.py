@@ -502,3 +502,57 @@ def test_binding_constants_match_the_header():
     assert e.value.status == la.binding.ERR_UNSUPPORTED
     assert _plan([4096], 64, 8, 128, la.BF16, la.KV_PADDED, num_cus=256, tile_shape=7).T_n == 128
     assert _plan([4096], 64, 8, 256, la.BF16, la.KV_PADDED, num_cus=256, tile_shape=8).T_n == 32
+
+
+def test_tail_spans_walk_matches_the_interval_arithmetic():
+    # short spans at the end of the line for a second class of workgroups: the plan's arithmetic and the walk
+    # against the oracle's cut points, on seeded batches, grids, tail sizes and shares
+    r = np.random.default_rng(77)
+    seen_tail = 0
+    for trial in range(200):
+        B = int(r.integers(1, 7))
+        Hkv = int(r.integers(1, 9))
+        seqlens = [int(r.integers(1, 30000))] * B if trial % 3 == 0 else [int(x) for x in r.integers(0, 30000, size=B)]
+        if sum(seqlens) == 0:
+            seqlens[0] = 777
+        layout = la.KV_PACKED if trial % 2 else la.KV_PADDED
+        G = int(r.choice([1, 2, 7, 64, 255, 256, 512]))
+        P = int(r.choice([1, 3, 16, 64, 256, 1000]))
+        permille = int(r.choice([0, 1, 30, 60, 250, 500]))
+        p = _plan(seqlens, Hkv, Hkv, 128, la.BF16, layout, num_cus=G, ctas_per_cu=1, grid=G, tail_grid=P,
+                  tail_permille=permille)
+        head_grid = p.grid - p.tail_grid
+        if p.tail_grid == 0:                      # too small a problem: plain stream-K spans
+            assert p.tail_iters == 0 and p.grid == min(G, p.total_iters)
+            assert p.total_iters - max(P, p.total_iters * (permille or 60) // 1000) < min(G, p.total_iters)
+            continue
+        seen_tail += 1
+        assert p.tail_grid == P and head_grid == min(G, p.total_iters)
+        assert p.tail_iters == max(P, p.total_iters * (permille or 60) // 1000)
+        head_iters = p.total_iters - p.tail_iters
+        assert (p.iters_per_cta, p.extra) == (head_iters // head_grid, head_iters % head_grid) and p.iters_per_cta >= 1
+        tail = (p.tail_grid, p.tail_iters)
+        edges = stream_k.span_edges(p.total_iters, head_grid, tail)
+        assert len(edges) == p.grid + 1 and edges[-1] == p.total_iters and np.all(np.diff(edges) >= 1)
+        work = stream_k.pieces(seqlens, Hkv, p.T_n, head_grid, "padded" if layout == la.KV_PADDED else "packed", tail)
+        stream_k.check_invariants(work, seqlens, Hkv, p.T_n)
+        want = {}
+        for t in work:
+            want.setdefault(t["cta"], []).append(t)
+        probe = sorted(set([0, head_grid - 1, head_grid, p.grid - 1] + [int(x) for x in r.integers(0, p.grid, size=8)]))
+        for g in probe:
+            got = la.lean_attn_walk(p, seqlens, Hkv, layout, g)
+            ref = want.get(g, [])
+            assert len(got) == len(ref), (trial, g)
+            for a, b in zip(got, ref):
+                assert (a["b"], a["h"], a["local_iter"], a["local_iter_end"], bool(a["host"]), bool(a["finishing"]),
+                        a["last_cta"]) == \
+                       (b["b"], b["h"], b["local_iter"], b["local_iter_end"], b["host"], b["finishing"], b["last_cta"]), \
+                    (trial, g)
+    assert seen_tail > 100
+    # limits: a tail with the baseline schedules is ignored, too many workgroups or too large a share are errors
+    assert _plan([5000] * 4, 8, 8, 128, la.BF16, la.KV_PADDED, num_cus=8, fixed_split=2, tail_grid=16).tail_grid == 0
+    for bad in (dict(grid=4000, tail_grid=200), dict(tail_grid=-1), dict(tail_grid=8, tail_permille=501)):
+        with pytest.raises(la.LeanAttnError) as e:
+            _plan([50000] * 4, 8, 8, 128, la.BF16, la.KV_PADDED, num_cus=256, **bad)
+        assert e.value.status == la.binding.ERR_TUNING
